@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-chunk Hierarchical Sparse Attention hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic chunk already resident in HBM:
+lf_chunk_budget (host) -> lf_select_mask -> lf_sparse_attn.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload last_chunk]
+
+value        effective TFLOP/s on kept blocks over the whole step (select + attention):
+             4 d sum_{kept (r,c)} rows_r cols_c valid-token FLOPs / wall time per step.
+roofline     dominant kernel (block-sparse attention, bf16 MFMA): the same FLOPs over the
+             kernel's own duration, HIP events on the launch stream inside the timed region.
+select       mask selection as an HBM-bound stage: one read of Q and K (bf16) per call.
+cpu_baseline the numpy oracle on the host cores, on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy kernel of known size); see profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _workloads():
+    from paper_2602_04789_amd import synth
+    return {"first_chunk": synth.cfg_first_chunk, "mid_rollout": synth.cfg_mid_rollout,
+            "last_chunk": synth.cfg_last_chunk, "tiny": synth.cfg_tiny}
+
+
+def kept_flops(lists: np.ndarray, w) -> float:
+    """4 d sum over kept (query block, KV block) pairs of valid rows x valid columns."""
+    nb, n, b = w.blocks_per_frame, w.frame_len, w.block
+    sizes = np.minimum(b, n - (np.arange(nb) * b))            # tokens per block within a frame
+    cols = sizes[lists % nb].sum(axis=-1)                     # [H, n_q] valid columns
+    rows = sizes[np.arange(lists.shape[1]) % nb]              # [n_q]
+    return float(4.0 * w.head_dim * (cols * rows[None, :]).sum())
+
+
+def cpu_baseline(w, x, lists_gpu, out_gpu, budget_s: float = 15.0):
+    """Time the oracle (as it stands) on a bounded sample: full mask selection, then attention
+    for (head, query block) pairs until the time budget is used."""
+    from oracle import hsa_oracle as O
+    from paper_2602_04789_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    Qf, Kf, Vf = (synth.bf16_bits_to_f32(x[k]) for k in "QKV")
+    ob = O.chunk_budget(w.chunk_idx, w.schedule)
+    t0 = time.perf_counter()
+    lists = O.select_mask(Qf, Kf, w.frame_len, w.block, ob)
+    t_sel = time.perf_counter() - t0
+    lists_match = bool(np.array_equal(lists, lists_gpu))
+    n_q = lists.shape[1]
+    rng = np.random.default_rng(0)
+    order = rng.permutation(w.heads * n_q)
+    t_attn, flops, done, worst = 0.0, 0.0, 0, 0.0
+    nb = w.blocks_per_frame
+    sizes = np.minimum(w.block, w.frame_len - np.arange(nb) * w.block)
+    for flat in order:
+        h, r = divmod(int(flat), n_q)
+        t1 = time.perf_counter()
+        ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, lists[h, r], w.frame_len, w.block)
+        t_attn += time.perf_counter() - t1
+        lo, hi = O.block_token_range(r, w.frame_len, w.block)
+        worst = max(worst, float(np.abs(out_gpu[h, lo:hi] - ref).max()))
+        flops += 4.0 * w.head_dim * float(sizes[r % nb]) * float(sizes[lists[h, r] % nb].sum())
+        done += 1
+        if t_sel + t_attn > budget_s:
+            break
+    frac = done / float(w.heads * n_q)
+    # whole-step time = full selection + attention extrapolated from the sampled pairs
+    est_step_s = t_sel + t_attn / frac
+    total_flops = flops / frac
+    return {
+        "value": total_flops / est_step_s / 1e12, "unit": "TFLOP/s", "cores": int(cores),
+        "kind": "oracle",
+        "sample": (f"full mask selection ({t_sel:.2f} s) + attention for {done} of "
+                   f"{w.heads * n_q} (head, query block) pairs ({t_attn:.2f} s), extrapolated "
+                   f"to the whole chunk: {est_step_s:.1f} s per step"),
+        "lists_match_gpu": lists_match, "sample_max_abs_err_gpu_vs_oracle": worst,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="last_chunk")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (heads would shard across GPUs "
+                 "without communication; no multi-GPU figure is produced). Use --gpus 1.")
+
+    import torch
+    from paper_2602_04789_amd import lf, synth
+    lf.load()   # raises if the HIP library is not built: there is no fallback path
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    w = _workloads()[args.workload]()
+    x = synth.make_inputs(w)
+    Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
+    sched = lf.make_schedule(w.schedule)
+    b = lf.lf_chunk_budget(w.chunk_idx, sched)
+    sh = lf.make_shape(Q, K, frame_len=w.frame_len, block=w.block)
+    ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+    nb = w.blocks_per_frame
+    idx = torch.empty((w.heads, w.frames_per_chunk * nb, b.list_len), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(Q)
+
+    def step():
+        bb = lf.lf_chunk_budget(w.chunk_idx, sched)
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
+        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        bb = lf.lf_chunk_budget(w.chunk_idx, sched)
+        ev[i][0].record()
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
+        ev[i][1].record()
+        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    lists = idx.cpu().numpy()
+    flops = kept_flops(lists, w)
+    tile_flops = 4.0 * 64 * 64 * w.head_dim * lists.size
+    sel_bytes = float((w.q_len + w.kv_len) * w.heads * w.head_dim * 2)
+    attn_tflops = flops / (attn_ms * 1e-3) / 1e12
+    sel_gbps = sel_bytes / (sel_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": "effective TFLOP/s on kept blocks, whole step (mask selection + block-sparse attention)",
+        "value": flops / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.heads} heads x {w.head_dim}, Q {w.q_len}, KV {w.kv_len} "
+                               f"({w.frames} frames x {w.frame_len}), block 64, "
+                               f"{b.list_len} of {w.frames * nb} KV blocks kept per query block",
+                   "heads": w.heads, "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len,
+                   "list_len": int(b.list_len), "k_blocks": int(b.k_blocks), "k_frames": int(b.k_frames)},
+        "ms_per_chunk": ms_step, "select_ms": sel_ms, "attn_ms": attn_ms,
+        "kept_gflop": flops / 1e9, "tile_gflop": tile_flops / 1e9,
+        "roofline": {"kernel": "lf_attn_kernel", "bound": "mfma", "achieved": attn_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "attn"))},
+        "select": {"bound": "hbm", "achieved": sel_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                   "frac": sel_gbps / PEAK_HBM_GBPS, "bytes": sel_bytes,
+                   "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "select"))},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, x, lists, out.float().cpu().numpy().astype(np.float64))
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,213 @@
+/*
+ * lf.h -- C ABI of the per-chunk Hierarchical Sparse Attention (HSA) hot path of
+ * "Light Forcing" for AMD MI355X (gfx950).
+ *
+ * The three calls follow the paper's statement of the problem (Sec. 4.1, Sec. 4.2):
+ *
+ *   lf_chunk_budget   Chunk-Aware Growth: chunk index + schedule -> integer keep-counts
+ *                     (Eq. 5, Eq. 6; appendix, implementation details of Light Forcing).
+ *   lf_select_mask    token compression, frame- and block-level scores and top-k
+ *                     (Eq. 7 - Eq. 12) -> sorted KV-block index lists per (head, query block).
+ *   lf_sparse_attn    blockwise sparse attention over the listed KV blocks (Eq. 13 / Eq. 3).
+ *
+ * Conventions
+ *   - Plain pointers and sizes only.  Every tensor pointer is DEVICE memory owned by the
+ *     caller; the library never allocates, frees or synchronises.  Calls enqueue kernels
+ *     on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     return at once.
+ *   - Return value: LF_OK (0) or a negative lf_status.  On error nothing is enqueued.
+ *   - Layout.  H heads (the caller folds batch into heads), d = head_dim, n = frame_len
+ *     tokens per frame, f frames per chunk, F_h history frames, F = F_h + f frames in the
+ *     cache.  Q is [H][q_len = f*n][d]; Kcache, Vcache are [H][kv_len = F*n][d] with the
+ *     current chunk's K/V as the LAST f frames (Sec. 4.2: k^{:i} includes chunk i).  d is
+ *     contiguous; token and head strides are given in elements.  Elements are bfloat16.
+ *     All base pointers and strides must keep every token row 16-byte aligned.
+ *   - Blocks (shapes stated after Eq. 7): every frame is cut into nb = ceil(n / block)
+ *     blocks; the last block of a frame holds n - (nb-1)*block tokens.  KV block id
+ *     c = tau*nb + j is block j of cache frame tau; query block r likewise within the
+ *     chunk.  n_q = f*nb query blocks, n_k = F*nb KV blocks.
+ */
+#ifndef LF_H
+#define LF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LF_OK = 0,
+  LF_ERR_NULL = -1,      /* a required pointer is NULL */
+  LF_ERR_SHAPE = -2,     /* sizes inconsistent or unsupported (see lf_shape) */
+  LF_ERR_BUDGET = -3,    /* budget inconsistent with the shape */
+  LF_ERR_DTYPE = -4,     /* dtype other than LF_BF16 */
+  LF_ERR_ALIGN = -5,     /* pointer or stride breaks the 16-byte row alignment */
+  LF_ERR_WORKSPACE = -6, /* workspace NULL or smaller than lf_workspace_bytes() */
+  LF_ERR_HIP = -7,       /* a HIP launch failed (hipGetLastError() was not hipSuccess) */
+  LF_ERR_SCHEDULE = -8   /* schedule fields out of range */
+} lf_status;
+
+typedef enum { LF_BF16 = 0 } lf_dtype;
+
+/* How the per-chunk keep ratio is chosen. */
+typedef enum {
+  LF_SCHED_FIXED = 0,  /* keep_fixed for every chunk */
+  LF_SCHED_LINEAR = 1, /* keep_first at chunk 1 ... keep_last at chunk n_chunks, linear */
+  LF_SCHED_CAG = 2     /* Chunk-Aware Growth: keep = 1 - s_i, s_i = s_base - beta/sqrt(i) (Eq. 5),
+                          beta from the FLOPs equality over chunks 2..n_chunks (Eq. 6) */
+} lf_sched_mode;
+
+/* What the keep ratio is a fraction of when it is turned into a block count. */
+typedef enum {
+  LF_OF_CANDIDATES = 0, /* of the candidate blocks B_r (Eq. 11) */
+  LF_OF_HISTORY = 1,    /* of all history blocks F_h*nb (clamped to |B_r|) */
+  LF_OF_ALL = 2         /* of all KV blocks n_k: the paper's sparsity ratio s_i */
+} lf_ratio_of;
+
+/* Everything known before the rollout starts (host memory, plain data). */
+typedef struct {
+  int32_t mode;              /* lf_sched_mode */
+  int32_t n_chunks;          /* chunks in the rollout (7 for a 5 s video) */
+  int32_t frames_per_chunk;  /* f (3 in the paper's experiments) */
+  int32_t frame_len;         /* n */
+  int32_t block;             /* b_q = b_kv (64 in the paper's experiments) */
+  int32_t n_sink;            /* earliest history frames always selected */
+  int32_t n_win;             /* nearest history frames always selected */
+  int32_t k_frames;          /* history frames retrieved by top-k from the candidate set M
+                                (= n_past_keep - n_sink - n_win in the appendix's terms) */
+  int32_t ratio_of;          /* lf_ratio_of */
+  int32_t current_mandatory; /* 1: every current-chunk block is kept and does not compete in
+                                the block top-k; 0: current-chunk blocks compete (Eq. 11 as
+                                written).  With no history they always compete. */
+  int32_t first_chunk_dense; /* 1: chunk 1 keeps every block (Sec. 4.1) */
+  int32_t reserved;          /* set to 0 */
+  double keep_fixed;         /* LF_SCHED_FIXED */
+  double keep_first;         /* LF_SCHED_LINEAR */
+  double keep_last;          /* LF_SCHED_LINEAR */
+  double s_base;             /* LF_SCHED_CAG (0.98 for 5 s videos) */
+  double s_target;           /* LF_SCHED_CAG (0.88 for 5 s videos) */
+} lf_schedule;
+
+/* Integer keep-counts of one chunk: all that mask selection needs (host memory). */
+typedef struct {
+  int32_t n_hist_frames;     /* F_h = (chunk_idx-1)*f */
+  int32_t frames_per_chunk;  /* f */
+  int32_t n_sink;            /* clamped to F_h */
+  int32_t n_win;             /* clamped to F_h - n_sink */
+  int32_t k_frames;          /* clamped to m = F_h - n_sink - n_win (footnote to Eq. 7):
+                                when m <= k_frames retrieval is inactive and all history
+                                frames are kept */
+  int32_t k_blocks;          /* size of the block top-k (Eq. 11) */
+  int32_t current_mandatory; /* effective value (0 when F_h == 0) */
+  int32_t list_len;          /* kept KV blocks per (head, query block)
+                                = k_blocks + (current_mandatory ? f*nb : 0) */
+  double keep_ratio;         /* the ratio the counts came from (informational) */
+} lf_budget;
+
+/* Tensor geometry shared by lf_select_mask and lf_sparse_attn (host memory). */
+typedef struct {
+  int32_t heads;     /* H >= 1 */
+  int32_t head_dim;  /* d: 64 or 128 */
+  int32_t frame_len; /* n >= 1 */
+  int32_t block;     /* 64 */
+  int32_t q_len;     /* f*n */
+  int32_t kv_len;    /* F*n, >= q_len, multiple of n */
+  int32_t dtype;     /* LF_BF16 */
+  int32_t reserved;  /* set to 0 */
+  int64_t q_stride_tok, q_stride_head; /* elements; multiples of 8 */
+  int64_t k_stride_tok, k_stride_head;
+  int64_t v_stride_tok, v_stride_head;
+  int64_t o_stride_tok, o_stride_head;
+} lf_shape;
+
+/*
+ * Chunk-Aware Growth (Sec. 4.1).  Host only; no GPU work.
+ *   chunk_idx  1-based index i of the chunk being generated.
+ *   schedule   in.   out: budget.
+ * keep ratio rho_i: FIXED / LINEAR as named above; CAG: rho_i = 1 - s_i with
+ *   alpha_i = 1/sqrt(i), w_i = l^q_i l^k_i d ~ i, beta = (s_base - s_target) * sum w_i /
+ *   sum(alpha_i w_i) over i = 2..n_chunks; chunk 1 keeps everything.
+ * counts: n_sink, n_win, k_frames clamped to the history as documented in lf_budget;
+ *   |B_r| = (n_sink + n_win + k_frames)*nb (+ f*nb when the current chunk competes);
+ *   k_blocks = ceil(rho_i * N - 1e-9) with N per ratio_of (for LF_OF_ALL with a mandatory
+ *   current chunk the f*nb current blocks are subtracted), clamped to [min(1,|B_r|), |B_r|].
+ * Errors: LF_ERR_NULL; LF_ERR_SCHEDULE (chunk_idx < 1, non-positive sizes, negative counts,
+ *   ratios outside [0, 1], unknown mode / ratio_of).
+ */
+int lf_chunk_budget(int32_t chunk_idx, const lf_schedule* schedule, lf_budget* budget);
+
+/* Bytes of device scratch lf_select_mask needs for this shape and budget (0 on bad input). */
+size_t lf_workspace_bytes(const lf_shape* shape, const lf_budget* budget);
+
+/*
+ * Where lf_select_mask leaves its intermediates inside the workspace, as byte offsets
+ * (for tests and profiling; contents are valid once the call's kernels have finished):
+ *   off[0]  q_tilde  float32 [H][n_q][d]   block means of Q            (Eq. 7)
+ *   off[1]  k_tilde  float32 [H][n_k][d]   block means of K            (Eq. 7)
+ *   off[2]  k_hat    float32 [H][m][d]     frame means of the candidate frames M,
+ *                                          ascending frame id          (Eq. 7)
+ * Returns LF_OK or the error lf_select_mask would return for the same shape/budget.
+ */
+int lf_workspace_layout(const lf_shape* shape, const lf_budget* budget, size_t off[3]);
+
+/*
+ * Mask selection (Sec. 4.2, Eq. 7 - Eq. 12), per head and per query block r:
+ *   q_tilde_r, k_tilde_c  block means (divide by the block's own token count);
+ *   k_hat_tau             mean of frame tau's nb block means, tau in M = history frames
+ *                         other than the n_sink earliest and the n_win nearest;
+ *   p_r[tau] = <q_tilde_r, k_hat_tau>;  T_r = top-k_frames(p_r) U sink U window U current;
+ *   B_r = blocks of the frames of T_r (without the current frames when current_mandatory);
+ *   o_r[c] = <q_tilde_r, k_tilde_c>;  J_r = top-k_blocks over B_r;
+ *   kept = J_r (U all current blocks when current_mandatory).
+ * Arithmetic (fixed so that lists are reproducible bit for bit): block sums exact
+ *   (binary64; exact for bfloat16 inputs with |x| = 0 or 2^-30 <= |x| < 2^8), means rounded
+ *   to float32; frame mean = binary64 sum of the nb float32 block means in ascending j,
+ *   divided by nb, rounded to float32; scores = binary64 sum over the head dimension in
+ *   ascending order of exact products, rounded to float32; top-k orders by larger score,
+ *   then lower index.  Inputs must be finite.
+ * Arguments
+ *   Q, Kcache     device, bfloat16, layout above (V is not read).
+ *   shape, budget host; budget as returned by lf_chunk_budget for this chunk
+ *                 (kv_len must equal (n_hist_frames + frames_per_chunk)*frame_len).
+ *   indices       device, int32 [H][n_q][list_len], written: ascending KV-block ids.
+ *   workspace     device scratch of >= lf_workspace_bytes(), 256-byte aligned.
+ * Errors: LF_ERR_NULL, LF_ERR_SHAPE, LF_ERR_DTYPE, LF_ERR_ALIGN, LF_ERR_BUDGET (counts
+ *   negative, exceeding their candidate sets, list_len inconsistent, more than 2048
+ *   candidate blocks or 1024 candidate frames), LF_ERR_WORKSPACE, LF_ERR_HIP.
+ */
+int lf_select_mask(const void* Q, const void* Kcache, const lf_shape* shape,
+                   const lf_budget* budget, int32_t* indices, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Blockwise sparse attention (Eq. 13): for every query token x of query block r
+ *   O_x = sum_y softmax_y(q_x . k_y * softmax_scale) v_y,
+ * y ranging over exactly the tokens of the KV blocks listed for (head, r); unlisted tiles
+ * are skipped, never materialised (Eq. 3 and the paragraph after it).  bf16 MFMA products,
+ * float32 online softmax and accumulation, bfloat16 output.
+ * Arguments
+ *   Q, Kcache, Vcache  device, bfloat16, layout above.
+ *   indices            device, int32 [H][n_q][list_len]; ids outside [0, n_k) are skipped;
+ *                      order is free, duplicates count twice.  list_len >= 1 and every list
+ *                      must hold at least one valid id.
+ *   softmax_scale      0 selects 1/sqrt(d).
+ *   O                  device, bfloat16 [H][q_len][d] with the o_ strides, written.
+ * Errors: LF_ERR_NULL, LF_ERR_SHAPE, LF_ERR_DTYPE, LF_ERR_ALIGN, LF_ERR_BUDGET
+ *   (list_len < 1), LF_ERR_HIP.
+ */
+int lf_sparse_attn(const void* Q, const void* Kcache, const void* Vcache,
+                   const lf_shape* shape, const int32_t* indices, int32_t list_len,
+                   float softmax_scale, void* O, void* hip_stream);
+
+/* Static, NUL-terminated description of an lf_status value. */
+const char* lf_strerror(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int lf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LF_H */

@@ -143,7 +143,7 @@ def chunk_budget(chunk_idx: int, sched) -> Budget:
     cur_mand = 1 if (sched.current_mandatory and F_h > 0) else 0
     n_tf = n_sink + n_win + k_frames                # selected history frames
     n_cand = n_tf * nb + (0 if cur_mand else f * nb)  # |B_r|
-    rho = keep_ratio(chunk_idx, sched)
+    rho = min(max(keep_ratio(chunk_idx, sched), 0.0), 1.0)
     if sched.ratio_of == OF_CANDIDATES:
         k_blocks = _ceil_count(rho, n_cand)
     elif sched.ratio_of == OF_HISTORY:

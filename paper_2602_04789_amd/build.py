@@ -1,0 +1,63 @@
+"""Compile the C-ABI library ``liblf_hsa.so`` for gfx950 with hipcc (in-tree).
+
+    python -m paper_2602_04789_amd.build
+
+hipcc cross-compiles without a GPU.  Device code is built with packed-FP32 VALU ops
+disabled; the host file is built with -ffp-contract=off because the budget arithmetic
+must round exactly as written.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "liblf_hsa.so")
+OBJ = os.path.join(PKG, "_build")
+
+SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip"]
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+          "-Wall", "-Wno-unused-function"]
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found (need ROCm)")
+    return exe
+
+
+def _run(cmd):
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout)
+        raise RuntimeError("build failed: " + " ".join(cmd))
+    return res.stdout
+
+
+def build(verbose: bool = False, extra_device_flags=()) -> str:
+    hipcc = _hipcc()
+    os.makedirs(OBJ, exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        path = os.path.join(CSRC, src)
+        obj = os.path.join(OBJ, src.replace(".", "_") + ".o")
+        if src.endswith(".hip"):
+            cmd = [hipcc, "-c", path, "-o", obj] + COMMON + DEVICE + list(extra_device_flags)
+        else:
+            cmd = [hipcc, "-x", "c++", "-c", path, "-o", obj, "-ffp-contract=off"] + COMMON
+        out = _run(cmd)
+        if verbose and out.strip():
+            print(out)
+        objs.append(obj)
+    _run([hipcc, "-shared", "-o", LIB] + objs + ["--offload-arch=gfx950"])
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose="-v" in sys.argv))

@@ -1,0 +1,32 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+#ifndef LF_COMMON_H
+#define LF_COMMON_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lf.h"
+
+#define LF_MAX_CAND_BLOCKS 2048  // |B_r| the selection kernel can rank in LDS
+#define LF_MAX_CAND_FRAMES 1024  // |M| the selection kernel can rank in LDS
+#define LF_MAX_HIST_FRAMES 4096  // F_h bound (flag array in LDS)
+
+// Derived sizes of one call; filled by lf_derive() after validation.
+struct lf_dims {
+  int H, d, n, f, F, F_h, nb, n_q, n_k, m;
+  int n_tf;     // selected history frames: n_sink + n_win + k_frames
+  int n_cand;   // |B_r|
+  size_t off_qt, off_kt, off_kh, ws_bytes;
+};
+
+// Validates shape (and budget when non-NULL); returns LF_OK or an lf_status.
+int lf_derive(const lf_shape* s, const lf_budget* b, lf_dims* out);
+
+// Kernel launchers (defined in the .hip files); return LF_OK or LF_ERR_HIP.
+int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_budget* b,
+                     const lf_dims* dm, int32_t* indices, void* workspace, void* stream);
+int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
+                   const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
+                   void* O, void* stream);
+
+#endif

@@ -1,0 +1,209 @@
+"""ctypes binding of the C-ABI library (``include/lf.h``): argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels.  PyTorch is used here
+for nothing but device memory (``torch.empty`` on the GPU) and the current HIP stream.
+There is no CPU fallback: if the shared library has not been built, or a call returns an
+error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblf_hsa.so")
+_lib = None
+
+LF_OK = 0
+LF_BF16 = 0
+LF_SCHED_FIXED, LF_SCHED_LINEAR, LF_SCHED_CAG = 0, 1, 2
+LF_OF_CANDIDATES, LF_OF_HISTORY, LF_OF_ALL = 0, 1, 2
+
+
+class lf_schedule(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("n_chunks", C.c_int32), ("frames_per_chunk", C.c_int32),
+                ("frame_len", C.c_int32), ("block", C.c_int32), ("n_sink", C.c_int32),
+                ("n_win", C.c_int32), ("k_frames", C.c_int32), ("ratio_of", C.c_int32),
+                ("current_mandatory", C.c_int32), ("first_chunk_dense", C.c_int32),
+                ("reserved", C.c_int32),
+                ("keep_fixed", C.c_double), ("keep_first", C.c_double), ("keep_last", C.c_double),
+                ("s_base", C.c_double), ("s_target", C.c_double)]
+
+
+class lf_budget(C.Structure):
+    _fields_ = [("n_hist_frames", C.c_int32), ("frames_per_chunk", C.c_int32),
+                ("n_sink", C.c_int32), ("n_win", C.c_int32), ("k_frames", C.c_int32),
+                ("k_blocks", C.c_int32), ("current_mandatory", C.c_int32), ("list_len", C.c_int32),
+                ("keep_ratio", C.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class lf_shape(C.Structure):
+    _fields_ = [("heads", C.c_int32), ("head_dim", C.c_int32), ("frame_len", C.c_int32),
+                ("block", C.c_int32), ("q_len", C.c_int32), ("kv_len", C.c_int32),
+                ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("q_stride_tok", C.c_int64), ("q_stride_head", C.c_int64),
+                ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+                ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+                ("o_stride_tok", C.c_int64), ("o_stride_head", C.c_int64)]
+
+
+class LfError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lf_strerror(status)} (lf_status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> C.CDLL:
+    """Load liblf_hsa.so (built by ``paper_2602_04789_amd.build``); raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2602_04789_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+    lib.lf_chunk_budget.argtypes = [C.c_int32, C.POINTER(lf_schedule), C.POINTER(lf_budget)]
+    lib.lf_chunk_budget.restype = C.c_int
+    lib.lf_workspace_bytes.argtypes = [C.POINTER(lf_shape), C.POINTER(lf_budget)]
+    lib.lf_workspace_bytes.restype = C.c_size_t
+    lib.lf_workspace_layout.argtypes = [C.POINTER(lf_shape), C.POINTER(lf_budget),
+                                        C.POINTER(C.c_size_t)]
+    lib.lf_workspace_layout.restype = C.c_int
+    lib.lf_select_mask.argtypes = [vp, vp, C.POINTER(lf_shape), C.POINTER(lf_budget), vp, vp,
+                                   C.c_size_t, vp]
+    lib.lf_select_mask.restype = C.c_int
+    lib.lf_sparse_attn.argtypes = [vp, vp, vp, C.POINTER(lf_shape), vp, C.c_int32, C.c_float,
+                                   vp, vp]
+    lib.lf_sparse_attn.restype = C.c_int
+    lib.lf_strerror.argtypes = [C.c_int]
+    lib.lf_strerror.restype = C.c_char_p
+    lib.lf_version.argtypes = []
+    lib.lf_version.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def lf_strerror(status: int) -> str:
+    return load().lf_strerror(int(status)).decode()
+
+
+def lf_version() -> int:
+    return int(load().lf_version())
+
+
+def make_schedule(s) -> lf_schedule:
+    """Build the C struct from any object with the struct's field names (e.g. synth.Schedule)."""
+    out = lf_schedule()
+    for name, _ in lf_schedule._fields_:
+        if name != "reserved":
+            setattr(out, name, getattr(s, name))
+    return out
+
+
+def lf_chunk_budget(chunk_idx: int, schedule) -> lf_budget:
+    sch = schedule if isinstance(schedule, lf_schedule) else make_schedule(schedule)
+    out = lf_budget()
+    rc = load().lf_chunk_budget(int(chunk_idx), C.byref(sch), C.byref(out))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_chunk_budget")
+    return out
+
+
+def make_shape(Q, K, V=None, O=None, frame_len: int = 0, block: int = 64) -> lf_shape:
+    """Geometry of [H, L, d] tensors (any object with .shape and .stride() in elements)."""
+    sh = lf_shape()
+    sh.heads, sh.q_len, sh.head_dim = int(Q.shape[0]), int(Q.shape[1]), int(Q.shape[2])
+    sh.kv_len = int(K.shape[1])
+    sh.frame_len, sh.block, sh.dtype = int(frame_len), int(block), LF_BF16
+    sh.q_stride_head, sh.q_stride_tok = int(Q.stride(0)), int(Q.stride(1))
+    sh.k_stride_head, sh.k_stride_tok = int(K.stride(0)), int(K.stride(1))
+    Vt = K if V is None else V
+    Ot = Q if O is None else O
+    sh.v_stride_head, sh.v_stride_tok = int(Vt.stride(0)), int(Vt.stride(1))
+    sh.o_stride_head, sh.o_stride_tok = int(Ot.stride(0)), int(Ot.stride(1))
+    return sh
+
+
+def lf_workspace_bytes(shape: lf_shape, budget: lf_budget) -> int:
+    return int(load().lf_workspace_bytes(C.byref(shape), C.byref(budget)))
+
+
+def lf_workspace_layout(shape: lf_shape, budget: lf_budget) -> Tuple[int, int, int]:
+    off = (C.c_size_t * 3)()
+    rc = load().lf_workspace_layout(C.byref(shape), C.byref(budget), off)
+    if rc != LF_OK:
+        raise LfError(rc, "lf_workspace_layout")
+    return int(off[0]), int(off[1]), int(off[2])
+
+
+def _check_tensor(t, name: str):
+    import torch
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in GPU memory")
+    if t.dtype != torch.bfloat16:
+        raise ValueError(f"{name} must be bfloat16")
+    if t.dim() != 3 or t.stride(2) != 1:
+        raise ValueError(f"{name} must be [H, L, d] with d contiguous")
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def lf_select_mask(Q, Kcache, frame_len: int, block: int, budget: lf_budget, indices=None,
+                   workspace=None, stream=None):
+    """Enqueue mask selection; returns the int32 [H, n_q, list_len] index tensor (device)."""
+    import torch
+    _check_tensor(Q, "Q")
+    _check_tensor(Kcache, "Kcache")
+    sh = make_shape(Q, Kcache, frame_len=frame_len, block=block)
+    lib = load()
+    need = lf_workspace_bytes(sh, budget)
+    nb = -(-frame_len // block)
+    n_q = (sh.q_len // frame_len) * nb if frame_len > 0 else 0
+    if indices is None:
+        indices = torch.empty((sh.heads, n_q, max(int(budget.list_len), 0)), dtype=torch.int32,
+                              device=Q.device)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    rc = lib.lf_select_mask(Q.data_ptr(), Kcache.data_ptr(), C.byref(sh), C.byref(budget),
+                            indices.data_ptr(), workspace.data_ptr(),
+                            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_select_mask")
+    return indices
+
+
+def lf_sparse_attn(Q, Kcache, Vcache, indices, frame_len: int, block: int,
+                   softmax_scale: float = 0.0, O=None, stream=None):
+    """Enqueue blockwise sparse attention; returns O (bfloat16 [H, q_len, d], device)."""
+    import torch
+    _check_tensor(Q, "Q")
+    _check_tensor(Kcache, "Kcache")
+    _check_tensor(Vcache, "Vcache")
+    if not indices.is_cuda or indices.dtype != torch.int32 or not indices.is_contiguous():
+        raise ValueError("indices must be a contiguous int32 GPU tensor [H, n_q, list_len]")
+    if O is None:
+        O = torch.empty_like(Q, memory_format=torch.contiguous_format)
+    _check_tensor(O, "O")
+    sh = make_shape(Q, Kcache, Vcache, O, frame_len=frame_len, block=block)
+    n_q = (sh.q_len // frame_len) * (-(-frame_len // block)) if frame_len > 0 else -1
+    if indices.dim() != 3 or indices.shape[0] != sh.heads or indices.shape[1] != n_q:
+        raise ValueError("indices must be [H, n_q, list_len]")
+    rc = load().lf_sparse_attn(Q.data_ptr(), Kcache.data_ptr(), Vcache.data_ptr(), C.byref(sh),
+                               indices.data_ptr(), int(indices.shape[-1]), float(softmax_scale),
+                               O.data_ptr(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_sparse_attn")
+    return O

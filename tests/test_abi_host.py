@@ -1,0 +1,157 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, lf_chunk_budget agrees with the oracle's budget on every schedule tried, and
+every argument error is reported before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import hsa_oracle as O
+from paper_2602_04789_amd import lf, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(lf.library_path()):
+        from paper_2602_04789_amd import build
+        build.build()
+    return lf.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    text = open(os.path.join(ROOT, "include", "lf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(lf_[a-z_]+)\s*\(", text))
+    assert {"lf_chunk_budget", "lf_select_mask", "lf_sparse_attn", "lf_workspace_bytes",
+            "lf_workspace_layout", "lf_strerror", "lf_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lf.lf_version() >= 100
+    assert lf.lf_strerror(0) == "ok" and "NULL" in lf.lf_strerror(-1)
+
+
+def test_struct_sizes_match_header(lib):
+    # 12 int32 + 5 double; 8 int32 + double; 8 int32 + 8 int64
+    assert C.sizeof(lf.lf_schedule) == 12 * 4 + 5 * 8
+    assert C.sizeof(lf.lf_budget) == 8 * 4 + 8
+    assert C.sizeof(lf.lf_shape) == 8 * 4 + 8 * 8
+
+
+def _all_schedules():
+    yield synth.cfg_tiny().schedule, range(1, 8)
+    yield synth.cfg_first_chunk().schedule, range(1, 8)
+    yield synth.cfg_mid_rollout().schedule, range(1, 8)
+    yield synth.cfg_last_chunk().schedule, range(1, 8)
+    yield synth.cfg_rollout(1, 0).schedule, range(1, 8)
+    yield synth.cfg_paper_5s(1).schedule, range(1, 8)
+    for mode in (0, 1, 2):
+        for ratio_of in (0, 1, 2):
+            for cm in (0, 1):
+                for fcd in (0, 1):
+                    for (ns, nw, kf) in ((0, 0, 0), (1, 2, 3), (2, 1, 1), (1, 1, 40)):
+                        for n, nch in ((1560, 7), (1536, 21), (200, 5), (64, 3)):
+                            yield synth.Schedule(mode=mode, n_chunks=nch, frames_per_chunk=3,
+                                                 frame_len=n, n_sink=ns, n_win=nw, k_frames=kf,
+                                                 ratio_of=ratio_of, current_mandatory=cm,
+                                                 first_chunk_dense=fcd, keep_fixed=0.37,
+                                                 keep_first=0.9, keep_last=0.15, s_base=0.95,
+                                                 s_target=0.85), range(1, nch + 1)
+
+
+def test_chunk_budget_matches_oracle(lib):
+    count = 0
+    for sch, chunks in _all_schedules():
+        for i in chunks:
+            got = lf.lf_chunk_budget(i, sch)
+            want = O.chunk_budget(i, sch)
+            for name in ("n_hist_frames", "frames_per_chunk", "n_sink", "n_win", "k_frames",
+                         "k_blocks", "current_mandatory", "list_len"):
+                assert getattr(got, name) == getattr(want, name), (sch, i, name)
+            assert got.keep_ratio == want.keep_ratio, (sch, i)   # bit-identical binary64
+            count += 1
+    assert count > 3000
+
+
+def test_chunk_budget_errors(lib):
+    s = lf.make_schedule(synth.cfg_last_chunk().schedule)
+    out = lf.lf_budget()
+    assert lib.lf_chunk_budget(1, None, C.byref(out)) == -1
+    assert lib.lf_chunk_budget(1, C.byref(s), None) == -1
+    assert lib.lf_chunk_budget(0, C.byref(s), C.byref(out)) == -8
+    for field, bad in (("mode", 7), ("ratio_of", -1), ("frames_per_chunk", 0), ("frame_len", 0),
+                       ("block", 0), ("n_sink", -1), ("k_frames", -2), ("keep_fixed", 1.5)):
+        t = lf.make_schedule(synth.cfg_last_chunk().schedule)
+        setattr(t, field, bad)
+        assert lib.lf_chunk_budget(2, C.byref(t), C.byref(out)) == -8, field
+
+
+def _good():
+    w = synth.cfg_last_chunk()
+    sh = lf.lf_shape()
+    sh.heads, sh.head_dim, sh.frame_len, sh.block = w.heads, w.head_dim, w.frame_len, 64
+    sh.q_len, sh.kv_len, sh.dtype = w.q_len, w.kv_len, 0
+    for t, L in (("q", w.q_len), ("k", w.kv_len), ("v", w.kv_len), ("o", w.q_len)):
+        setattr(sh, f"{t}_stride_tok", w.head_dim)
+        setattr(sh, f"{t}_stride_head", w.head_dim * L)
+    return w, sh, lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+
+
+FAKE = 0x10000  # a non-NULL, 256-byte aligned address that is never dereferenced on error paths
+
+
+def test_workspace_size_and_layout(lib):
+    w, sh, b = _good()
+    need = lf.lf_workspace_bytes(sh, b)
+    nb = 25
+    assert need >= 4 * w.heads * w.head_dim * (3 * nb + 21 * nb + 15)
+    o = lf.lf_workspace_layout(sh, b)
+    assert o[0] == 0 and o[0] < o[1] < o[2] < need and all(x % 256 == 0 for x in o)
+    b.k_blocks += 1                      # list_len no longer consistent
+    assert lf.lf_workspace_bytes(sh, b) == 0
+
+
+def test_select_mask_argument_errors_enqueue_nothing(lib):
+    w, sh, b = _good()
+    need = lf.lf_workspace_bytes(sh, b)
+    call = lambda Q=FAKE, K=FAKE, s=sh, bb=b, idx=FAKE, ws=FAKE, nbytes=need: lib.lf_select_mask(
+        Q, K, C.byref(s) if s is not None else None, C.byref(bb) if bb is not None else None,
+        idx, ws, nbytes, None)
+    assert call(Q=None) == -1 and call(K=None) == -1 and call(idx=None) == -1
+    assert call(s=None) == -1 and call(bb=None) == -1
+    assert call(ws=None) == -6 and call(nbytes=need - 1) == -6
+    assert call(Q=FAKE + 2) == -5 and call(ws=FAKE + 16) == -5
+    for field, bad, code in (("block", 32, -2), ("head_dim", 96, -2), ("dtype", 1, -4),
+                             ("q_len", w.q_len + 1, -2), ("kv_len", w.frame_len, -2),
+                             ("heads", 0, -2), ("k_stride_tok", 129, -5), ("k_stride_tok", 64, -2)):
+        _, s2, _ = _good()
+        setattr(s2, field, bad)
+        assert call(s=s2) == code, field
+    for field, bad in (("k_blocks", 151), ("k_blocks", -1), ("k_frames", 16), ("n_sink", 17),
+                       ("list_len", 187), ("n_hist_frames", 17), ("current_mandatory", 2)):
+        _, _, b2 = _good()
+        setattr(b2, field, bad)
+        assert call(bb=b2) == -3, field
+
+
+def test_sparse_attn_argument_errors_enqueue_nothing(lib):
+    w, sh, b = _good()
+    call = lambda Q=FAKE, K=FAKE, V=FAKE, s=sh, idx=FAKE, ll=188, sc=0.0, Out=FAKE: \
+        lib.lf_sparse_attn(Q, K, V, C.byref(s) if s is not None else None, idx, ll, sc, Out, None)
+    assert call(Q=None) == -1 and call(K=None) == -1 and call(V=None) == -1
+    assert call(idx=None) == -1 and call(Out=None) == -1 and call(s=None) == -1
+    assert call(ll=0) == -3
+    assert call(sc=-1.0) == -2 and call(sc=float("nan")) == -2
+    assert call(V=FAKE + 8) == -5
+    _, s2, _ = _good()
+    s2.head_dim = 256
+    assert call(s=s2) == -2
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(lf, "_lib", None)
+    monkeypatch.setattr(lf, "_LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        lf.lf_chunk_budget(1, synth.cfg_tiny().schedule)

@@ -1,0 +1,266 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bars: index lists, pooled block/frame means -- bit-exact; attention output -- max-abs 2e-2 and
+mean-abs 2e-3 against the binary64 oracle (bf16 inputs, bf16 output)."""
+import numpy as np
+import pytest
+
+from oracle import hsa_oracle as O
+from paper_2602_04789_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_04789_amd import lf
+    lf.load()
+    return torch, lf
+
+
+def _dev(torch, bits):
+    return torch.from_numpy(bits).view(torch.bfloat16).cuda()
+
+
+def _host_f32(bits):
+    return synth.bf16_bits_to_f32(bits)
+
+
+def _run_select(torch, lf, w, x, check_intermediates=True):
+    """GPU lists vs oracle lists (all heads, all query blocks); returns (gpu tensors, lists)."""
+    Q, K, V = (_dev(torch, x[k]) for k in "QKV")
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    ob = O.chunk_budget(w.chunk_idx, w.schedule)
+    assert b.list_len == ob.list_len and b.k_blocks == ob.k_blocks
+    sh = lf.make_shape(Q, K, frame_len=w.frame_len, block=w.block)
+    ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+    idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b, workspace=ws)
+    torch.cuda.synchronize()
+    want, I = O.select_mask(_host_f32(x["Q"]), _host_f32(x["K"]), w.frame_len, w.block, ob,
+                            return_intermediates=True)
+    if check_intermediates:
+        off = lf.lf_workspace_layout(sh, b)
+        H, d = w.heads, w.head_dim
+        raw = ws.cpu().numpy()
+        for name, o, cnt in (("q_tilde", off[0], I["q_tilde"].shape[1]),
+                             ("k_tilde", off[1], I["k_tilde"].shape[1]),
+                             ("k_hat", off[2], I["k_hat"].shape[1] if ob.k_frames < len(I["M"]) else 0)):
+            if cnt == 0:
+                continue
+            got = raw[o:o + H * cnt * d * 4].view(np.float32).reshape(H, cnt, d)
+            assert np.array_equal(got.view(np.uint32), I[name].view(np.uint32)), name
+    got = idx.cpu().numpy()
+    assert got.shape == want.shape and got.dtype == np.int32
+    bad = np.argwhere((got != want).any(axis=-1))
+    assert bad.size == 0, f"{len(bad)} of {got.shape[0] * got.shape[1]} lists differ, first {bad[:3]}"
+    return (Q, K, V), idx, want
+
+
+def _check_attn(torch, lf, w, x, dev, idx, lists, pairs=None):
+    Q, K, V = dev
+    out = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    Qf, Kf, Vf = (_host_f32(x[k]) for k in "QKV")
+    nb = w.blocks_per_frame
+    n_q = w.frames_per_chunk * nb
+    if pairs is None:
+        pairs = [(h, r) for h in range(w.heads) for r in range(n_q)]
+    worst, total, count = 0.0, 0.0, 0
+    for h, r in pairs:
+        lo, hi = O.block_token_range(r, w.frame_len, w.block)
+        ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, lists[h, r], w.frame_len, w.block)
+        err = np.abs(got[h, lo:hi] - ref)
+        worst = max(worst, float(err.max()))
+        total += float(err.sum())
+        count += err.size
+    mean = total / count
+    assert worst <= MAX_ABS and mean <= MEAN_ABS, (worst, mean)
+    return got, worst, mean
+
+
+def _sample_pairs(w, k, seed=0):
+    rng = np.random.default_rng(seed)
+    nb = w.blocks_per_frame
+    n_q = w.frames_per_chunk * nb
+    pairs = {(0, 0), (w.heads - 1, n_q - 1), (w.heads // 2, nb - 1)}   # includes ragged query blocks
+    while len(pairs) < k:
+        pairs.add((int(rng.integers(w.heads)), int(rng.integers(n_q))))
+    return sorted(pairs)
+
+
+# ----------------------------------------------------------------------------- small cases, all outputs
+
+SMALL = {
+    "tiny": lambda: synth.cfg_tiny(),
+    "ragged_c1": lambda: synth.small_ragged(chunk_idx=1, current_mandatory=0),
+    "ragged_c2": lambda: synth.small_ragged(chunk_idx=2),
+    "ragged_c4": lambda: synth.small_ragged(chunk_idx=4),
+    "ragged_c6_d64": lambda: synth.small_ragged(chunk_idx=6, head_dim=64, heads=2),
+    "ragged_compete": lambda: synth.small_ragged(chunk_idx=4, current_mandatory=0,
+                                                 ratio_of=synth.OF_ALL, keep_fixed=0.3),
+    "aligned_1536_c3": lambda: synth.scaled(synth.cfg_paper_5s(3, heads=2)),
+    "one_token_tail": lambda: synth.small_ragged(frame_len=129, chunk_idx=3, heads=2),
+    "short_frame": lambda: synth.small_ragged(frame_len=40, chunk_idx=5, heads=2, k_frames=1),
+    "many_frames": lambda: synth.small_ragged(frame_len=64, chunk_idx=40, frames_per_chunk=2,
+                                              heads=1, k_frames=5, n_sink=2, n_win=3),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_cases_match_oracle_everywhere(gpu, name):
+    torch, lf = gpu
+    w = SMALL[name]()
+    x = synth.make_inputs(w)
+    print(f"case {name}: H={w.heads} d={w.head_dim} n={w.frame_len} F={w.frames}", flush=True)
+    dev, idx, lists = _run_select(torch, lf, w, x)
+    _check_attn(torch, lf, w, x, dev, idx, lists)
+
+
+def test_ties_resolve_to_lower_index(gpu):
+    """Duplicate history frames and duplicate blocks: equal float32 scores everywhere."""
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=5, heads=2, k_frames=2, keep_fixed=0.3)
+    x = synth.make_inputs(w)
+    n = w.frame_len
+    K = x["K"]
+    K[:, 3 * n:4 * n] = K[:, 2 * n:3 * n]          # frame 3 := frame 2
+    K[:, 4 * n:5 * n] = K[:, 2 * n:3 * n]          # frame 4 := frame 2
+    K[:, 2 * n + 64:2 * n + 128] = K[:, 2 * n:2 * n + 64]   # block 1 := block 0 inside frame 2
+    K[:, n:2 * n] = 0                               # an all-zero frame: scores of +0.0 / -0.0
+    dev, idx, lists = _run_select(torch, lf, w, x)
+    _check_attn(torch, lf, w, x, dev, idx, lists)
+
+
+def test_full_budget_equals_dense_attention(gpu):
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=3, heads=2)
+    x = synth.make_inputs(w)
+    Q, K, V = (_dev(torch, x[k]) for k in "QKV")
+    lists = O.full_lists(w.heads, w.frame_len, w.block, w.frames_per_chunk, w.frames)
+    idx = torch.from_numpy(lists).cuda()
+    out = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block)
+    ref = torch.nn.functional.scaled_dot_product_attention(Q.float(), K.float(), V.float())
+    torch.cuda.synchronize()
+    err = (out.float() - ref).abs()
+    assert err.max().item() <= MAX_ABS and err.mean().item() <= MEAN_ABS
+
+
+def test_attention_list_edge_cases(gpu):
+    """Single tail block; unordered list; out-of-range ids skipped; duplicate id counted twice;
+    head-strided (non-contiguous) tensors; explicit softmax scale."""
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=3, heads=2)
+    x = synth.make_inputs(w)
+    Qf, Kf, Vf = (_host_f32(x[k]) for k in "QKV")
+    nb, n_q, n_k = w.blocks_per_frame, w.frames_per_chunk * w.blocks_per_frame, w.frames * w.blocks_per_frame
+    # tensors carved out of a larger buffer: head stride != q_len * d, token stride != d
+    def strided(bits):
+        H, L, d = bits.shape
+        buf = torch.zeros((H, L + 5, d + 8), dtype=torch.bfloat16, device="cuda")
+        view = buf[:, 2:2 + L, :d]
+        view.copy_(_dev(torch, bits))
+        return view
+    Q, K, V = strided(x["Q"]), strided(x["K"]), strided(x["V"])
+    Obuf = torch.zeros((w.heads, w.q_len + 3, w.head_dim + 8), dtype=torch.bfloat16, device="cuda")
+    Oview = Obuf[:, 1:1 + w.q_len, :w.head_dim]
+
+    cases = {
+        "single_tail_block": np.full((w.heads, n_q, 1), nb - 1, np.int32),
+        "unordered": np.tile(np.array([n_k - 1, 0, 5, 2], np.int32), (w.heads, n_q, 1)),
+        "invalid_ids_skipped": np.tile(np.array([-1, 3, n_k, 1 << 30, 4], np.int32), (w.heads, n_q, 1)),
+        "duplicate": np.tile(np.array([2, 2, 7], np.int32), (w.heads, n_q, 1)),
+    }
+    for name, lists in cases.items():
+        print("edge case", name, flush=True)
+        idx = torch.from_numpy(lists).cuda()
+        scale = 0.05 if name == "unordered" else 0.0
+        out = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, softmax_scale=scale, O=Oview)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().astype(np.float64)
+        for h in range(w.heads):
+            for r in range(n_q):
+                kept = [int(c) for c in lists[h, r] if 0 <= c < n_k]
+                lo, hi = O.block_token_range(r, w.frame_len, w.block)
+                ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, kept, w.frame_len, w.block,
+                                               scale=(scale if scale else None))
+                err = np.abs(got[h, lo:hi] - ref)
+                assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (name, h, r, err.max())
+    # nothing outside the O view was touched
+    assert float(Obuf[:, 0].abs().max()) == 0 and float(Obuf[:, :, w.head_dim:].abs().max()) == 0
+
+
+def test_calls_are_deterministic(gpu):
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=4)
+    x = synth.make_inputs(w)
+    Q, K, V = (_dev(torch, x[k]) for k in "QKV")
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    i1 = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    o1 = lf.lf_sparse_attn(Q, K, V, i1, w.frame_len, w.block)
+    i2 = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    o2 = lf.lf_sparse_attn(Q, K, V, i2, w.frame_len, w.block)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i2) and torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+def test_binding_rejects_bad_arguments(gpu):
+    torch, lf = gpu
+    w = synth.cfg_tiny()
+    x = synth.make_inputs(w)
+    Q, K, V = (_dev(torch, x[k]) for k in "QKV")
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    with pytest.raises(lf.LfError):
+        lf.lf_select_mask(Q, K, w.frame_len + 1, w.block, b)
+    with pytest.raises(lf.LfError):
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, b,
+                          workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(ValueError):
+        lf.lf_select_mask(Q.float(), K, w.frame_len, w.block, b)
+    with pytest.raises(ValueError):
+        lf.lf_sparse_attn(Q, K, V, torch.zeros((1, 1, 1), dtype=torch.int32, device="cuda"),
+                          w.frame_len, w.block)
+
+
+# ----------------------------------------------------------------------------- full-size configurations
+
+FULL = {
+    "first_chunk": synth.cfg_first_chunk,
+    "mid_rollout": synth.cfg_mid_rollout,
+    "last_chunk": synth.cfg_last_chunk,
+}
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_configs(gpu, name):
+    """Benchmark shapes in the launch configuration the benchmark times: every index list
+    against the oracle, attention on sampled (head, query block) pairs computed one by one."""
+    torch, lf = gpu
+    w = FULL[name]()
+    print(f"config {name}: generating", flush=True)
+    x = synth.make_inputs(w)
+    print("select parity", flush=True)
+    dev, idx, lists = _run_select(torch, lf, w, x)
+    print("attention parity (sampled)", flush=True)
+    got, worst, mean = _check_attn(torch, lf, w, x, dev, idx, lists, pairs=_sample_pairs(w, 16))
+    print(f"{name}: max-abs {worst:.2e} mean-abs {mean:.2e}", flush=True)
+    # size-independent properties on the whole output: finite; |O| bounded by max |V|
+    vmax = float(np.abs(_host_f32(x["V"])).max())
+    assert np.abs(got).max() <= vmax * 1.01
+
+
+@pytest.mark.parametrize("chunk", [1, 2, 3, 7])
+def test_rollout_calls_40_heads(gpu, chunk):
+    torch, lf = gpu
+    w = synth.cfg_rollout(chunk, step=1)
+    print(f"rollout chunk {chunk}: generating", flush=True)
+    x = synth.make_inputs(w)
+    dev, idx, lists = _run_select(torch, lf, w, x, check_intermediates=False)
+    print("attention parity (sampled)", flush=True)
+    _check_attn(torch, lf, w, x, dev, idx, lists, pairs=_sample_pairs(w, 8, seed=chunk))
