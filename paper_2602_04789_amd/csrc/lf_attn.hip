@@ -40,27 +40,35 @@ struct AttnArgs {
 union Frag {
   uint4 u;
   bf16x8 v;
-  uint16_t h[8];
 };
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// 16-byte chunk swizzles of the LDS tiles (row = token within the tile, ch = 8-channel chunk).
+// K is read row-wise, 16 bytes per lane, 16 consecutive rows at one logical chunk: XOR with
+// the row spreads them over all banks.  V is read with the transposing 8-byte LDS read, four
+// consecutive rows x 64 bytes at a time: XOR moves each of the four rows to its own 64 bytes.
+template <int CH> __device__ __forceinline__ int k_swz(int row, int ch) { return ch ^ (row & (CH - 1)); }
+template <int CH> __device__ __forceinline__ int v_swz(int row, int ch) {
+  return ch ^ ((row & (CH / 4 - 1)) << 2);
 }
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
-  constexpr int CH = D / 8;             // 16-byte chunks per token row
-  constexpr int KS = D / 16;            // k-steps of S^T = K Q^T
-  constexpr int MB = D / 32;            // 32-row blocks of O^T
-  constexpr int LPT = 64 * CH / kThreads;  // 16-byte loads per thread, per tile, per tensor
-  constexpr int RPP = kThreads / CH;    // tile rows covered per load pass
+  constexpr int CH = D / 8;                 // 16-byte chunks per token row
+  constexpr int KS = D / 16;                // k-steps of S^T = K Q^T
+  constexpr int MB = D / 32;                // 32-row blocks of O^T
+  constexpr int RPI = 64 / CH;              // tile rows one wavefront load instruction covers
+  constexpr int LPW = 64 / (RPI * 4);       // load instructions per wavefront, per tile, per tensor
+  constexpr int TILE = 64 * CH;             // uint4 per tile
 
-  __shared__ uint4 smem[2 * 64 * CH];   // K tile | V tile; reused for the final merge
+  // Two tile buffers (K | V each) as separate LDS objects, so that the compiler can tell
+  // the asynchronous fill of one from the reads of the other; lds0 is reused for the merge.
+  __shared__ uint4 lds0[2 * TILE];
+  __shared__ uint4 lds1[2 * TILE];
   __shared__ float ml[2][2][64];
-  uint4* Ks = smem;
-  uint4* Vs = smem + 64 * CH;
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -92,27 +100,31 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
   const uint16_t* Kh = a.K + (int64_t)h * a.k_stride_head;
   const uint16_t* Vh = a.V + (int64_t)h * a.v_stride_head;
-  const int ld_row = tid / CH, ld_ch = tid % CH;
 
-  uint4 kreg[LPT], vreg[LPT];
-  auto fetch = [&](int t) -> int {
-    const int c = list[t];
+  // Tile load, global -> LDS without passing through registers: load instruction i of
+  // wavefront `wave` fills tile rows [RPI*(LPW*wave+i), +RPI); lane l lands at byte 16*l
+  // of that 1 KiB stripe, so it fetches the chunk the swizzle assigns to that place.  Rows
+  // past the block's token count re-read its last token (finite data that the mask removes).
+  const int ld_r = lane / CH, ld_p = lane % CH;
+  auto fetch = [&](int t, uint4* kb) -> int {
+    int c = list[t];
     const bool ok = (unsigned)c < (unsigned)a.n_k;
-    const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+    c = ok ? c : 0;
+    const int tau = c / a.nb, j = c % a.nb;
     const int tok0 = tau * a.n + j * 64;
-    const int cnt = ok ? min(64, a.n - j * 64) : 0;
+    const int cnt = min(64, a.n - j * 64);
+    uint4* vb = kb + TILE;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int row = ld_row + RPP * i;
-      if (row < cnt) {
-        kreg[i] = *reinterpret_cast<const uint4*>(Kh + (int64_t)(tok0 + row) * a.k_stride_tok + ld_ch * 8);
-        vreg[i] = *reinterpret_cast<const uint4*>(Vh + (int64_t)(tok0 + row) * a.v_stride_tok + ld_ch * 8);
-      } else {
-        kreg[i] = make_uint4(0, 0, 0, 0);
-        vreg[i] = make_uint4(0, 0, 0, 0);
-      }
+    for (int i = 0; i < LPW; ++i) {
+      const int row0 = RPI * (LPW * wave + i);
+      const int row = row0 + ld_r;
+      const int srow = min(row, cnt - 1);
+      const uint16_t* kp = Kh + (int64_t)(tok0 + srow) * a.k_stride_tok + k_swz<CH>(row, ld_p) * 8;
+      const uint16_t* vp = Vh + (int64_t)(tok0 + srow) * a.v_stride_tok + v_swz<CH>(row, ld_p) * 8;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kp), LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vp), LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
     }
-    return cnt;
+    return ok ? cnt : 0;
   };
 
   f32x16 oacc[MB];
@@ -122,18 +134,14 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
   float m_run = -1.0e30f, l_run = 0.0f;
 
-  int cnt_next = fetch(0);
-  for (int t = 0; t < a.list_len; ++t) {
+  int cnt_next = fetch(0, lds0);
+  // One tile: wait for it, start the next tile's fill into the other buffer, compute.
+  auto tile = [&](int t, const uint4* Ks, uint4* other) __attribute__((always_inline)) {
     const int cnt = cnt_next;
-    __syncthreads();  // every wavefront has finished reading the previous tile
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int row = ld_row + RPP * i;
-      Ks[row * CH + (ld_ch ^ (row & (CH - 1)))] = kreg[i];
-      Vs[row * CH + (ld_ch ^ (((row >> 2) & 1) << 2))] = vreg[i];
-    }
-    __syncthreads();
-    if (t + 1 < a.list_len) cnt_next = fetch(t + 1);
+    __builtin_amdgcn_s_waitcnt(0);  // this wavefront's part of tile t has landed in LDS
+    __syncthreads();                // ... and everyone's; the other buffer is no longer being read
+    if (t + 1 < a.list_len) cnt_next = fetch(t + 1, other);
+    const uint4* Vs = Ks + TILE;
 
     // S^T[kv, q] for this wavefront's 32 KV rows x 32 query rows.
     f32x16 sacc;
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         Frag kf;
-        kf.u = Ks[row * CH + ((2 * s + kg) ^ (row & (CH - 1)))];
+        kf.u = Ks[row * CH + k_swz<CH>(row, 2 * s + kg)];
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[s].v, sacc, 0, 0, 0);
       }
     }
@@ -179,31 +187,40 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 
     // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
     // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
+    // The A operand (V^T) comes from the row-major V tile through the transposing LDS
+    // read: within each group of 16 lanes, lane 4e+g supplies the address of row e,
+    // columns 4g..4g+3, and lane i receives column i of the four rows.
     const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(Vs);
+    const int i16 = lane & 15;
+    const int tr_row = 32 * kh + 4 * kg + (i16 >> 2);
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      Frag pf;
+      bf16x8 pf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf.h[e] = f32_to_bf16_rne(p[8 * u + e]);
+      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[8 * u + e];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        const int col = 32 * mb + ln;
-        Frag vf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int row = 32 * kh + 16 * u + 8 * (e >> 2) + 4 * kg + (e & 3);
-          const int chunk = (col >> 3) ^ (((row >> 2) & 1) << 2);
-          vf.h[e] = Vs16[(row * CH + chunk) * 8 + (col & 7)];
-        }
-        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, oacc[mb], 0, 0, 0);
+        const int col = 32 * mb + tr_col;
+        const int r0 = tr_row + 16 * u, r1 = r0 + 8;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            LDS_PTR(bf16x4, Vs16 + (r0 * CH + v_swz<CH>(r0, col >> 3)) * 8 + (col & 7)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            LDS_PTR(bf16x4, Vs16 + (r1 * CH + v_swz<CH>(r1, col >> 3)) * 8 + (col & 7)));
+        const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
       }
     }
+  };
+  for (int t = 0; t < a.list_len; t += 2) {
+    tile(t, lds0, lds1);
+    if (t + 1 < a.list_len) tile(t + 1, lds1, lds0);
   }
 
   // Merge the two KV halves: wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine.
   l_run += __shfl_xor(l_run, 32);
   __syncthreads();
-  float* mbuf = reinterpret_cast<float*>(smem);  // [rh][MB*16][64]
+  float* mbuf = reinterpret_cast<float*>(lds0);  // [rh][MB*16][64]
   if (kh == 1) {
     ml[rh][0][lane] = m_run;
     ml[rh][1][lane] = l_run;
@@ -224,17 +241,14 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          uint16_t o4[4];
+          bf16x4 o4;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * g + e;
             const float o2 = mbuf[(rh * MB * 16 + mb * 16 + i) * 64 + lane];
-            o4[e] = f32_to_bf16_rne((oacc[mb][i] * a1 + o2 * a2) * inv);
+            o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
           }
-          uint2 pk;
-          pk.x = (uint32_t)o4[0] | ((uint32_t)o4[1] << 16);
-          pk.y = (uint32_t)o4[2] | ((uint32_t)o4[3] << 16);
-          *reinterpret_cast<uint2*>(op + 32 * mb + 8 * g + 4 * kg) = pk;
+          *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
         }
       }
     }
