@@ -23,6 +23,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
+constexpr int kMaxEnt = 512;  // list entries decoded per pass (power of two)
 
 struct AttnArgs {
   const uint16_t* Q;
@@ -69,6 +70,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   __shared__ uint4 lds0[2 * TILE];
   __shared__ uint4 lds1[2 * TILE];
   __shared__ float ml[2][2][64];
+  __shared__ int2 ent[kMaxEnt];            // (first token, token count) per list entry
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -98,33 +100,53 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   }
 
   const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
-  const uint16_t* Kh = a.K + (int64_t)h * a.k_stride_head;
-  const uint16_t* Vh = a.V + (int64_t)h * a.v_stride_head;
+  const char* Kh = reinterpret_cast<const char*>(a.K + (int64_t)h * a.k_stride_head);
+  const char* Vh = reinterpret_cast<const char*>(a.V + (int64_t)h * a.v_stride_head);
+  const int64_t k_row_bytes = a.k_stride_tok * 2, v_row_bytes = a.v_stride_tok * 2;
 
   // Tile load, global -> LDS without passing through registers: load instruction i of
   // wavefront `wave` fills tile rows [RPI*(LPW*wave+i), +RPI); lane l lands at byte 16*l
   // of that 1 KiB stripe, so it fetches the chunk the swizzle assigns to that place.  Rows
   // past the block's token count re-read its last token (finite data that the mask removes).
+  // Per-lane byte offsets inside a full tile are loop invariants.
   const int ld_r = lane / CH, ld_p = lane % CH;
-  auto fetch = [&](int t, uint4* kb) -> int {
-    int c = list[t];
-    const bool ok = (unsigned)c < (unsigned)a.n_k;
-    c = ok ? c : 0;
-    const int tau = c / a.nb, j = c % a.nb;
-    const int tok0 = tau * a.n + j * 64;
-    const int cnt = min(64, a.n - j * 64);
-    uint4* vb = kb + TILE;
+  uint32_t koff[LPW], voff[LPW], kswz[LPW], vswz[LPW];
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      const int row0 = RPI * (LPW * wave + i);
-      const int row = row0 + ld_r;
-      const int srow = min(row, cnt - 1);
-      const uint16_t* kp = Kh + (int64_t)(tok0 + srow) * a.k_stride_tok + k_swz<CH>(row, ld_p) * 8;
-      const uint16_t* vp = Vh + (int64_t)(tok0 + srow) * a.v_stride_tok + v_swz<CH>(row, ld_p) * 8;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kp), LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vp), LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
+  for (int i = 0; i < LPW; ++i) {
+    const int row = RPI * (LPW * wave + i) + ld_r;
+    kswz[i] = (uint32_t)k_swz<CH>(row, ld_p) * 16u;
+    vswz[i] = (uint32_t)v_swz<CH>(row, ld_p) * 16u;
+    koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + kswz[i];
+    voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + vswz[i];
+  }
+  // (first token, token count) of list entry t, wavefront-uniform.
+  auto entry = [&](int t) -> int2 {
+    const int2 e = ent[t & (kMaxEnt - 1)];
+    return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+  };
+  auto fetch = [&](int2 e, uint4* kb) {
+    const char* kbase = Kh + (int64_t)e.x * k_row_bytes;
+    const char* vbase = Vh + (int64_t)e.x * v_row_bytes;
+    uint4* vb = kb + TILE;
+    if (e.y == 64) {
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) {
+        const int row0 = RPI * (LPW * wave + i);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + koff[i]), LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + voff[i]), LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
+      }
+    } else {
+      const int last = max(e.y - 1, 0);
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) {
+        const int row0 = RPI * (LPW * wave + i);
+        const uint32_t srow = (uint32_t)min(row0 + ld_r, last);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + (srow * (uint32_t)k_row_bytes + kswz[i])),
+                                         LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + (srow * (uint32_t)v_row_bytes + vswz[i])),
+                                         LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
+      }
     }
-    return ok ? cnt : 0;
   };
 
   f32x16 oacc[MB];
@@ -134,13 +156,29 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
   float m_run = -1.0e30f, l_run = 0.0f;
 
-  int cnt_next = fetch(0, lds0);
+  // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
+  // an id outside [0, n_k) becomes an empty block (count 0).
+  for (int t0 = 0; t0 < a.list_len; t0 += kMaxEnt) {
+  const int t1 = min(a.list_len, t0 + kMaxEnt);
+  __syncthreads();
+  for (int i = t0 + tid; i < t1; i += kThreads) {
+    const int c = list[i];
+    const bool ok = (unsigned)c < (unsigned)a.n_k;
+    const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+    ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+  }
+  __syncthreads();
+  int2 e_cur = entry(t0);
+  fetch(e_cur, lds0);
+  int2 e_next = entry(min(t0 + 1, t1 - 1));
   // One tile: wait for it, start the next tile's fill into the other buffer, compute.
   auto tile = [&](int t, const uint4* Ks, uint4* other) __attribute__((always_inline)) {
-    const int cnt = cnt_next;
+    const int cnt = e_cur.y;
     __builtin_amdgcn_s_waitcnt(0);  // this wavefront's part of tile t has landed in LDS
     __syncthreads();                // ... and everyone's; the other buffer is no longer being read
-    if (t + 1 < a.list_len) cnt_next = fetch(t + 1, other);
+    if (t + 1 < t1) fetch(e_next, other);
+    e_cur = e_next;
+    e_next = entry(min(t + 2, t1 - 1));
     const uint4* Vs = Ks + TILE;
 
     // S^T[kv, q] for this wavefront's 32 KV rows x 32 query rows.
@@ -212,9 +250,10 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       }
     }
   };
-  for (int t = 0; t < a.list_len; t += 2) {
+  for (int t = t0; t < t1; t += 2) {
     tile(t, lds0, lds1);
-    if (t + 1 < a.list_len) tile(t + 1, lds1, lds0);
+    if (t + 1 < t1) tile(t + 1, lds1, lds0);
+  }
   }
 
   // Merge the two KV halves: wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine.
