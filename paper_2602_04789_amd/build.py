@@ -22,7 +22,10 @@ OBJ = os.path.join(PKG, "_build")
 SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
-DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          # keep MFMA accumulators in ordinary VGPRs (the attention kernel runs one wavefront
+          # per SIMD; the AGPR form costs copies around every vector-ALU use)
+          "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def _hipcc() -> str:

@@ -1,11 +1,14 @@
 // Blockwise sparse attention for gfx950 (Eq. 13; Eq. 3 and the paragraph after it: only
 // listed tiles are computed, the element mask is never materialised).
 //
-// One workgroup (4 wavefronts) per (head, query block of 64 rows).  For each listed KV
-// block the 64 x d K and V tiles are staged in LDS; wavefront (rh, kh) owns query rows
-// [32 rh, 32 rh + 32) and KV rows [32 kh, 32 kh + 32) of every tile and keeps its own
-// online-softmax state (m, l, O), so no data crosses wavefronts inside the loop; the two
-// KV halves are merged once at the end.
+// One workgroup (4 wavefronts) per (head, query block of 64 rows); two workgroups share a
+// compute unit, so every SIMD holds two wavefronts in different phases and the matrix core
+// of one overlaps the vector ALU of the other.  For each listed KV block the 64 x d K and V
+// tiles are brought into a double-buffered LDS tile by asynchronous global->LDS loads that
+// are issued a few at a time between the compute phases of the previous tile.  Wavefront
+// (rh, kh) owns query rows [32 rh, 32 rh + 32) and KV rows [32 kh, 32 kh + 32) of every tile
+// and keeps its own online-softmax state (m, l, O), so nothing crosses wavefronts inside
+// the loop; the two KV halves are merged once at the end.
 //
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with
 // v_mfma_f32_32x32x16_bf16: in the 32x32 accumulator layout a lane then holds one query
@@ -20,7 +23,9 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int int32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kMaxEnt = 512;  // list entries decoded per pass (power of two)
@@ -35,6 +40,7 @@ struct AttnArgs {
   int64_t v_stride_tok, v_stride_head, o_stride_tok, o_stride_head;
   int n, nb, n_q, n_k, list_len;
   int total_wg, wg_per_xcd;
+  int k_extent, v_extent;  // bytes of one head's K / V, first to last element
   float c;  // softmax_scale * log2(e)
 };
 
@@ -43,9 +49,12 @@ union Frag {
   bf16x8 v;
 };
 
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory operations
+// of this wavefront are outstanding and does not wait on the other counters.
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 // 16-byte chunk swizzles of the LDS tiles (row = token within the tile, ch = 8-channel chunk).
 // K is read row-wise, 16 bytes per lane, 16 consecutive rows at one logical chunk: XOR with
@@ -54,6 +63,14 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 template <int CH> __device__ __forceinline__ int k_swz(int row, int ch) { return ch ^ (row & (CH - 1)); }
 template <int CH> __device__ __forceinline__ int v_swz(int row, int ch) {
   return ch ^ ((row & (CH / 4 - 1)) << 2);
+}
+
+// Workgroup barrier that orders LDS accesses only; the global->LDS loads are waited for
+// explicitly (s_waitcnt vmcnt) by the wavefront that issued them, just before the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
 template <int D>
@@ -65,12 +82,10 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   constexpr int LPW = 64 / (RPI * 4);       // load instructions per wavefront, per tile, per tensor
   constexpr int TILE = 64 * CH;             // uint4 per tile
 
-  // Two tile buffers (K | V each) as separate LDS objects, so that the compiler can tell
-  // the asynchronous fill of one from the reads of the other; lds0 is reused for the merge.
-  __shared__ uint4 lds0[2 * TILE];
-  __shared__ uint4 lds1[2 * TILE];
+  __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles; reused for the final merge
+  __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
   __shared__ float ml[2][2][64];
-  __shared__ int2 ent[kMaxEnt];            // (first token, token count) per list entry
+  __shared__ int2 ent[kMaxEnt];             // (first token, token count) per list entry
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -110,44 +125,88 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // past the block's token count re-read its last token (finite data that the mask removes).
   // Per-lane byte offsets inside a full tile are loop invariants.
   const int ld_r = lane / CH, ld_p = lane % CH;
-  uint32_t koff[LPW], voff[LPW], kswz[LPW], vswz[LPW];
+  uint32_t koff[LPW], voff[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     const int row = RPI * (LPW * wave + i) + ld_r;
-    kswz[i] = (uint32_t)k_swz<CH>(row, ld_p) * 16u;
-    vswz[i] = (uint32_t)v_swz<CH>(row, ld_p) * 16u;
-    koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + kswz[i];
-    voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + vswz[i];
+    koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + (uint32_t)k_swz<CH>(row, ld_p) * 16u;
+    voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + (uint32_t)v_swz<CH>(row, ld_p) * 16u;
   }
   // (first token, token count) of list entry t, wavefront-uniform.
   auto entry = [&](int t) -> int2 {
     const int2 e = ent[t & (kMaxEnt - 1)];
     return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
   };
-  auto fetch = [&](int2 e, uint4* kb) {
-    const char* kbase = Kh + (int64_t)e.x * k_row_bytes;
-    const char* vbase = Vh + (int64_t)e.x * v_row_bytes;
-    uint4* vb = kb + TILE;
+  // The loads are buffer loads (resource = this head's K or V, scalar offset = the tile's
+  // first token, vector offset = the lane's place in the tile): no per-load address math.
+  // They are issued from inline assembly, a few at a time between the compute phases of the
+  // current tile, so that the vector-memory queue never backs up into the issuing wavefront.
+  auto make_rsrc = [](const char* base, int bytes) {
+    int32x4 r;
+    const uint64_t b = (uint64_t)base;
+    r[0] = (int)(uint32_t)b;
+    r[1] = (int)(uint32_t)(b >> 32);  // stride 0: raw buffer
+    r[2] = bytes;
+    r[3] = 0x00020000;
+    return r;
+  };
+  const int32x4 krs = make_rsrc(Kh, a.k_extent), vrs = make_rsrc(Vh, a.v_extent);
+  auto dma16 = [](int32x4 rs, uint32_t lds_addr, uint32_t voff, uint32_t soff) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff));
+  };
+  // Loads i0 .. i1-1 (of LPW) of this wavefront's share of one tile.
+  auto fetch_part = [&](int2 e, uint4* dst, int32x4 rs, uint32_t row_bytes, const uint32_t (&off)[LPW],
+                        bool is_k, int i0, int i1) __attribute__((always_inline)) {
+    const uint32_t base = (uint32_t)e.x * row_bytes;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
     if (e.y == 64) {
 #pragma unroll
-      for (int i = 0; i < LPW; ++i) {
-        const int row0 = RPI * (LPW * wave + i);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + koff[i]), LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + voff[i]), LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
-      }
+      for (int i = i0; i < i1; ++i) dma16(rs, lds0 + i * 1024, off[i], base);
     } else {
       const int last = max(e.y - 1, 0);
 #pragma unroll
-      for (int i = 0; i < LPW; ++i) {
-        const int row0 = RPI * (LPW * wave + i);
-        const uint32_t srow = (uint32_t)min(row0 + ld_r, last);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(kbase + (srow * (uint32_t)k_row_bytes + kswz[i])),
-                                         LDS_PTR(void, kb + row0 * CH), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLOBAL_PTR(vbase + (srow * (uint32_t)v_row_bytes + vswz[i])),
-                                         LDS_PTR(void, vb + row0 * CH), 16, 0, 0);
+      for (int i = i0; i < i1; ++i) {
+        const int row = RPI * (LPW * wave + i) + ld_r;
+        const uint32_t swz = (uint32_t)(is_k ? k_swz<CH>(row, ld_p) : v_swz<CH>(row, ld_p)) * 16u;
+        dma16(rs, lds0 + i * 1024, (uint32_t)min(row, last) * row_bytes + swz, base);
       }
     }
   };
+  auto fetch_k = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
+    fetch_part(e, buf, krs, (uint32_t)k_row_bytes, koff, true, i0, i1);
+  };
+  auto fetch_v = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
+    fetch_part(e, buf + TILE, vrs, (uint32_t)v_row_bytes, voff, false, i0, i1);
+  };
+
+  // LDS addresses of this lane's operand fragments inside a tile (loop invariants).
+  // K (A operand of S^T): row 32 kh + ln, logical chunk 2 s + kg.
+  int kaddr[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const int row = 32 * kh + ln;
+    kaddr[s] = row * CH + k_swz<CH>(row, 2 * s + kg);
+  }
+  // V^T (A operand of O^T) through the transposing LDS read: within each group of 16 lanes,
+  // lane 4e+g supplies the address of row e, columns 4g..4g+3, and lane i receives column i
+  // of the four rows.  vaddr[u][half][mb] is in units of bf16 elements.
+  int vaddr[2][2][MB];
+  {
+    const int i16 = lane & 15;
+    const int tr_row = 32 * kh + 4 * kg + (i16 >> 2);
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const int row = tr_row + 16 * u + 8 * hf, col = 32 * mb + tr_col;
+          vaddr[u][hf][mb] = (row * CH + v_swz<CH>(row, col >> 3)) * 8 + (col & 7);
+        }
+  }
 
   f32x16 oacc[MB];
 #pragma unroll
@@ -155,139 +214,144 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
   float m_run = -1.0e30f, l_run = 0.0f;
+  constexpr int H1 = (LPW + 1) / 2;  // loads issued in the first of the two slots of a phase
 
   // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
   // an id outside [0, n_k) becomes an empty block (count 0).
   for (int t0 = 0; t0 < a.list_len; t0 += kMaxEnt) {
-  const int t1 = min(a.list_len, t0 + kMaxEnt);
-  __syncthreads();
-  for (int i = t0 + tid; i < t1; i += kThreads) {
-    const int c = list[i];
-    const bool ok = (unsigned)c < (unsigned)a.n_k;
-    const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
-    ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
-  }
-  __syncthreads();
-  int2 e_cur = entry(t0);
-  fetch(e_cur, lds0);
-  int2 e_next = entry(min(t0 + 1, t1 - 1));
-  // One tile: wait for it, start the next tile's fill into the other buffer, compute.
-  auto tile = [&](int t, const uint4* Ks, uint4* other) __attribute__((always_inline)) {
-    const int cnt = e_cur.y;
-    __builtin_amdgcn_s_waitcnt(0);  // this wavefront's part of tile t has landed in LDS
-    __syncthreads();                // ... and everyone's; the other buffer is no longer being read
-    if (t + 1 < t1) fetch(e_next, other);
-    e_cur = e_next;
-    e_next = entry(min(t + 2, t1 - 1));
-    const uint4* Vs = Ks + TILE;
+    const int t1 = min(a.list_len, t0 + kMaxEnt);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    for (int i = t0 + tid; i < t1; i += kThreads) {
+      const int c = list[i];
+      const bool ok = (unsigned)c < (unsigned)a.n_k;
+      const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+      ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+    }
+    __syncthreads();
+    int2 e_cur = entry(t0);
+    fetch_k(e_cur, buf0, 0, LPW);
+    fetch_v(e_cur, buf0, 0, LPW);
+    int2 e_next = entry(min(t0 + 1, t1 - 1));
 
-    // S^T[kv, q] for this wavefront's 32 KV rows x 32 query rows.
-    f32x16 sacc;
+    // One tile: wait for it, then compute it while the next tile's loads are issued, in four
+    // slots, into the other buffer.
+    auto tile = [&](int t, const uint4* cur, uint4* other) __attribute__((always_inline)) {
+      const int cnt = e_cur.y;
+      const bool more = t + 1 < t1;
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of tile t has landed
+      lds_barrier();                             // ... everyone's has; `other` is no longer read
+      if (more) fetch_k(e_next, other, 0, H1);
+
+      // S^T[kv, q] for this wavefront's 32 KV rows x 32 query rows.
+      f32x16 sacc;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
-    {
-      const int row = 32 * kh + ln;
+      for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
+      {
+        Frag kf[KS];
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        Frag kf;
-        kf.u = Ks[row * CH + k_swz<CH>(row, 2 * s + kg)];
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[s].v, sacc, 0, 0, 0);
+        for (int s = 0; s < KS; ++s) kf[s].u = cur[kaddr[s]];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[s].v, sacc, 0, 0, 0);
       }
-    }
-    // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
-    if (cnt < 64) {
+      if (more) fetch_k(e_next, other, H1, LPW);
+      // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
+      if (cnt < 64) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kv = 32 * kh + 8 * (i >> 2) + 4 * kg + (i & 3);
-        if (kv >= cnt) sacc[i] = -INFINITY;
+        for (int i = 0; i < 16; ++i) {
+          const int kv = 32 * kh + 8 * (i >> 2) + 4 * kg + (i & 3);
+          if (kv >= cnt) sacc[i] = -INFINITY;
+        }
       }
-    }
-    float mx = sacc[0];
+      float mx = fmaxf(fmaxf(sacc[0], sacc[1]), fmaxf(sacc[2], sacc[3]));
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * a.c);
-    if (__ballot(m_new > m_run) != 0ull) {
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
+      for (int i = 4; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sacc[i], sacc[i + 1]));
+      {
+        // lanes l and l+32 hold the same query column: exchange through the lane-swap unit
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+      }
+      const float m_new = fmaxf(m_run, mx * a.c);
+      if (__ballot(m_new > m_run) != 0ull) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
+        m_run = m_new;
+      }
+      if (more) fetch_v(e_next, other, 0, H1);
+
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -m_run));
+
+      // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
+      // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
+      const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(cur + TILE);
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[8 * u + e];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr[u][0][mb]));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr[u][1][mb]));
+          const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
+        }
+      }
+      if (more) fetch_v(e_next, other, H1, LPW);
+      l_run += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])) +
+               (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
+      e_cur = e_next;
+      e_next = entry(min(t + 2, t1 - 1));
+    };
+    for (int t = t0; t < t1; t += 2) {
+      tile(t, buf0, buf1);
+      if (t + 1 < t1) tile(t + 1, buf1, buf0);
+    }
+  }
+
+  // Merge the two KV halves, one query-row half at a time through one LDS buffer:
+  // wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine and store.
+  l_run += __shfl_xor(l_run, 32);
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  float* mbuf = reinterpret_cast<float*>(buf0);  // [MB*16][64]
+  for (int phase = 0; phase < 2; ++phase) {
+    __syncthreads();
+    if (kh == 1 && rh == phase) {
+      ml[rh][0][lane] = m_run;
+      ml[rh][1][lane] = l_run;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
-      m_run = m_new;
+        for (int i = 0; i < 16; ++i) mbuf[(mb * 16 + i) * 64 + lane] = oacc[mb][i];
     }
-    float p[16];
+    __syncthreads();
+    if (kh == 0 && rh == phase) {
+      const float m2 = ml[rh][0][lane], l2 = ml[rh][1][lane];
+      const float m = fmaxf(m_run, m2);
+      const float a1 = __builtin_amdgcn_exp2f(m_run - m), a2 = __builtin_amdgcn_exp2f(m2 - m);
+      const float inv = 1.0f / (l_run * a1 + l2 * a2);
+      if (qrow < q_cnt) {
+        uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      p[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -m_run));
-      l_run += p[i];
-    }
-
-    // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
-    // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
-    // The A operand (V^T) comes from the row-major V tile through the transposing LDS
-    // read: within each group of 16 lanes, lane 4e+g supplies the address of row e,
-    // columns 4g..4g+3, and lane i receives column i of the four rows.
-    const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(Vs);
-    const int i16 = lane & 15;
-    const int tr_row = 32 * kh + 4 * kg + (i16 >> 2);
-    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      bf16x8 pf;
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 o4;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[8 * u + e];
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const int col = 32 * mb + tr_col;
-        const int r0 = tr_row + 16 * u, r1 = r0 + 8;
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            LDS_PTR(bf16x4, Vs16 + (r0 * CH + v_swz<CH>(r0, col >> 3)) * 8 + (col & 7)));
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            LDS_PTR(bf16x4, Vs16 + (r1 * CH + v_swz<CH>(r1, col >> 3)) * 8 + (col & 7)));
-        const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
-      }
-    }
-  };
-  for (int t = t0; t < t1; t += 2) {
-    tile(t, lds0, lds1);
-    if (t + 1 < t1) tile(t + 1, lds1, lds0);
-  }
-  }
-
-  // Merge the two KV halves: wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine.
-  l_run += __shfl_xor(l_run, 32);
-  __syncthreads();
-  float* mbuf = reinterpret_cast<float*>(lds0);  // [rh][MB*16][64]
-  if (kh == 1) {
-    ml[rh][0][lane] = m_run;
-    ml[rh][1][lane] = l_run;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mbuf[(rh * MB * 16 + mb * 16 + i) * 64 + lane] = oacc[mb][i];
-  }
-  __syncthreads();
-  if (kh == 0) {
-    const float m2 = ml[rh][0][lane], l2 = ml[rh][1][lane];
-    const float m = fmaxf(m_run, m2);
-    const float a1 = __builtin_amdgcn_exp2f(m_run - m), a2 = __builtin_amdgcn_exp2f(m2 - m);
-    const float inv = 1.0f / (l_run * a1 + l2 * a2);
-    if (qrow < q_cnt) {
-      uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 o4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int i = 4 * g + e;
-            const float o2 = mbuf[(rh * MB * 16 + mb * 16 + i) * 64 + lane];
-            o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
+            for (int e = 0; e < 4; ++e) {
+              const int i = 4 * g + e;
+              const float o2 = mbuf[(mb * 16 + i) * 64 + lane];
+              o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
+            }
+            *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
           }
-          *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
         }
       }
     }
@@ -321,6 +385,8 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
   a.total_wg = dm->H * dm->n_q;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   a.c = scale * 1.4426950408889634f;
+  a.k_extent = (int)(((int64_t)s->kv_len - 1) * s->k_stride_tok * 2 + dm->d * 2);
+  a.v_extent = (int)(((int64_t)s->kv_len - 1) * s->v_stride_tok * 2 + dm->d * 2);
   const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
   hipStream_t st = (hipStream_t)stream;
   if (dm->d == 128)

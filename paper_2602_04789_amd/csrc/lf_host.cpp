@@ -121,6 +121,11 @@ int lf_derive(const lf_shape* s, const lf_budget* b, lf_dims* o) {
   if (s->q_stride_tok < s->head_dim || s->k_stride_tok < s->head_dim ||
       s->v_stride_tok < s->head_dim || s->o_stride_tok < s->head_dim)
     return LF_ERR_SHAPE;
+  // one head's K and V must each span less than 2 GiB (32-bit buffer offsets in the kernels)
+  const int64_t lim = ((int64_t)1 << 31) - 1;
+  if (((int64_t)s->kv_len - 1) * s->k_stride_tok * 2 + s->head_dim * 2 > lim ||
+      ((int64_t)s->kv_len - 1) * s->v_stride_tok * 2 + s->head_dim * 2 > lim)
+    return LF_ERR_SHAPE;
   memset(o, 0, sizeof(*o));
   o->H = s->heads;
   o->d = s->head_dim;
