@@ -144,10 +144,13 @@ size_t lf_workspace_bytes(const lf_shape* shape, const lf_budget* budget);
 /*
  * Where lf_select_mask leaves its intermediates inside the workspace, as byte offsets
  * (for tests and profiling; contents are valid once the call's kernels have finished):
- *   off[0]  q_tilde  float32 [H][n_q][d]   block means of Q            (Eq. 7)
- *   off[1]  k_tilde  float32 [H][n_k][d]   block means of K            (Eq. 7)
- *   off[2]  k_hat    float32 [H][m][d]     frame means of the candidate frames M,
- *                                          ascending frame id          (Eq. 7)
+ *   off[0]  q_tilde  float32 [H][n_q][d]      block means of Q          (Eq. 7)
+ *   off[1]  k_tilde  float32 [H][d/4][n_k][4] block means of K          (Eq. 7)
+ *   off[2]  k_hat    float32 [H][d/4][m][4]   frame means of the candidate frames M,
+ *                                             ascending frame id        (Eq. 7)
+ * k_tilde and k_hat are stored channel-quad major: channel t of row c sits at
+ * [t/4][c][t%4], so that the scoring kernel reads 16 bytes per row and step, coalesced
+ * over neighbouring rows.
  * Returns LF_OK or the error lf_select_mask would return for the same shape/budget.
  */
 int lf_workspace_layout(const lf_shape* shape, const lf_budget* budget, size_t off[3]);

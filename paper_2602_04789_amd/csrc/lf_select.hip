@@ -4,8 +4,8 @@
 //                         over the bf16 inputs, HBM-bound.
 //   lf_frame_mean_kernel  frame means of the candidate frames (Eq. 7, framewise).
 //   lf_select_kernel      per (head, query block): frame scores (Eq. 8), frame top-k
-//                         (Eq. 9), block scores (Eq. 10), block top-k by a bitonic sort in
-//                         LDS (Eq. 11), ascending index list (Eq. 12).
+//                         (Eq. 9), block scores (Eq. 10), block top-k by a bitonic sort over
+//                         lane shuffles and LDS (Eq. 11), ascending index list (Eq. 12).
 //
 // Arithmetic contract (see lf.h): block sums in binary64 (exact for in-range bf16 inputs,
 // so the reduction tree is free), means rounded to float32; scores are binary64 sums over
@@ -32,6 +32,15 @@ struct PoolArgs {
   int n, nb, n_q, n_k;
 };
 
+// Pooled keys are stored "channel-quad major": element (row c, channel t) of a [rows][d]
+// matrix lives at ((t/4) * rows + c) * 4 + t%4.  A thread that walks one row's channels in
+// order then reads 16 bytes per step, and neighbouring rows (= neighbouring threads) are
+// contiguous, so the score loops below read straight from global memory with coalesced
+// 16-byte loads and need no staging.
+__device__ __forceinline__ int64_t quad_major(int rows, int c, int t) {
+  return ((int64_t)(t >> 2) * rows + c) * 4 + (t & 3);
+}
+
 // One workgroup per block of <= 64 tokens.  Thread t owns 8 consecutive channels
 // (one 16-byte load per token) of every (256/CH)-th token.
 template <int D>
@@ -53,22 +62,26 @@ __global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
   const int64_t stride = is_q ? a.q_stride_tok : a.k_stride_tok;
   const int ch = threadIdx.x % CH, rg = threadIdx.x / CH;
 
+  uint4 v[64 / RG];
+#pragma unroll
+  for (int i = 0; i < 64 / RG; ++i) {
+    const int row = rg + RG * i;
+    v[i] = row < cnt ? *reinterpret_cast<const uint4*>(src + (int64_t)(tok0 + row) * stride + ch * 8)
+                     : make_uint4(0, 0, 0, 0);
+  }
   double acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.0;
 #pragma unroll
-  for (int row = rg; row < 64; row += RG) {
-    if (row < cnt) {
-      const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)(tok0 + row) * stride + ch * 8);
-      acc[0] += (double)bf16lo(v.x);
-      acc[1] += (double)bf16hi(v.x);
-      acc[2] += (double)bf16lo(v.y);
-      acc[3] += (double)bf16hi(v.y);
-      acc[4] += (double)bf16lo(v.z);
-      acc[5] += (double)bf16hi(v.z);
-      acc[6] += (double)bf16lo(v.w);
-      acc[7] += (double)bf16hi(v.w);
-    }
+  for (int i = 0; i < 64 / RG; ++i) {
+    acc[0] += (double)bf16lo(v[i].x);
+    acc[1] += (double)bf16hi(v[i].x);
+    acc[2] += (double)bf16lo(v[i].y);
+    acc[3] += (double)bf16hi(v[i].y);
+    acc[4] += (double)bf16lo(v[i].z);
+    acc[5] += (double)bf16hi(v[i].z);
+    acc[6] += (double)bf16lo(v[i].w);
+    acc[7] += (double)bf16hi(v[i].w);
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) red[rg][ch * 8 + i] = acc[i];
@@ -77,22 +90,42 @@ __global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
     double s = 0.0;
 #pragma unroll
     for (int g = 0; g < RG; ++g) s += red[g][threadIdx.x];
-    float* dst = is_q ? a.qt + ((int64_t)h * a.n_q + c) * D : a.kt + ((int64_t)h * a.n_k + c) * D;
-    dst[threadIdx.x] = (float)(s / (double)cnt);
+    const float mean = (float)(s / (double)cnt);
+    if (is_q)
+      a.qt[((int64_t)h * a.n_q + c) * D + threadIdx.x] = mean;
+    else
+      a.kt[(int64_t)h * a.n_k * D + quad_major(a.n_k, c, threadIdx.x)] = mean;
   }
 }
 
 // k_hat[h][a][:] for candidate frame tau = n_sink + a: binary64 sum of the frame's nb block
-// means in ascending block order, / nb, rounded to float32.
+// means in ascending block order, / nb, rounded to float32.  One thread per channel quad.
 __global__ void lf_frame_mean_kernel(const float* __restrict__ kt, float* __restrict__ kh,
                                      int d, int nb, int n_k, int m, int n_sink) {
   const int h = blockIdx.x / m, a = blockIdx.x % m;
   const int tau = n_sink + a;
-  const float* src = kt + ((int64_t)h * n_k + (int64_t)tau * nb) * d;
-  for (int t = threadIdx.x; t < d; t += blockDim.x) {
-    double s = 0.0;
-    for (int j = 0; j < nb; ++j) s += (double)src[(int64_t)j * d + t];
-    kh[((int64_t)h * m + a) * d + t] = (float)(s / (double)nb);
+  for (int q = threadIdx.x; q < d / 4; q += blockDim.x) {
+    const float4* src = reinterpret_cast<const float4*>(kt + (int64_t)h * n_k * d) +
+                        ((int64_t)q * n_k + (int64_t)tau * nb);
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int j = 0;
+    for (; j + 8 <= nb; j += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = src[j + u];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        s0 += (double)v[u].x; s1 += (double)v[u].y; s2 += (double)v[u].z; s3 += (double)v[u].w;
+      }
+    }
+    for (; j < nb; ++j) {
+      const float4 v = src[j];
+      s0 += (double)v.x; s1 += (double)v.y; s2 += (double)v.z; s3 += (double)v.w;
+    }
+    float4 o;
+    o.x = (float)(s0 / (double)nb); o.y = (float)(s1 / (double)nb);
+    o.z = (float)(s2 / (double)nb); o.w = (float)(s3 / (double)nb);
+    reinterpret_cast<float4*>(kh + (int64_t)h * m * d)[(int64_t)q * m + a] = o;
   }
 }
 
@@ -103,20 +136,39 @@ struct SelectArgs {
   int32_t* indices;
   int d, nb, n_q, n_k, F_h, f, m;
   int n_sink, n_win, k_frames, k_blocks, current_mandatory, list_len;
-  int n_cand, n_cand_pow2;
+  int n_cand, n_tf;
 };
 
-// <q, k> over the head dimension, ascending, binary64 accumulate (products are exact).
+// Dynamic LDS of lf_select_kernel<D, E>; must mirror the carving at the top of the kernel.
+inline size_t select_lds_bytes(const SelectArgs& a, int e) {
+  size_t b = (size_t)a.d * sizeof(double);
+  b += (size_t)kThreads * e * (sizeof(float) + sizeof(int));   // exchange arrays of the sort
+  b += (size_t)a.m * sizeof(float);
+  b += (size_t)(a.n_tf + a.f) * sizeof(int);
+  b += (size_t)((a.F_h + 3) & ~3) + (size_t)((a.n_cand + 3) & ~3);
+  return b;
+}
+
+// <q_tilde, row> over the head dimension in ascending order, binary64 accumulate (the product
+// of two float32 is exact in binary64, so only the order matters), rounded to float32 once.
+// `row` points at channel quad 0 of the row in a quad-major matrix with `rows` rows.
 template <int D>
-__device__ __forceinline__ float dot_seq(const double* __restrict__ qd, const float* __restrict__ k) {
+__device__ __forceinline__ float dot_quad_major(const double* __restrict__ qd,
+                                                const float4* __restrict__ row, int rows) {
   double acc = 0.0;
-#pragma unroll 8
-  for (int t = 0; t < D; t += 4) {
-    const float4 kv = *reinterpret_cast<const float4*>(k + t);
-    acc += qd[t + 0] * (double)kv.x;
-    acc += qd[t + 1] * (double)kv.y;
-    acc += qd[t + 2] * (double)kv.z;
-    acc += qd[t + 3] * (double)kv.w;
+#pragma unroll 1
+  for (int q0 = 0; q0 < D / 4; q0 += 16) {
+    float4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = row[(int64_t)(q0 + u) * rows];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int t = 4 * (q0 + u);
+      acc += qd[t + 0] * (double)v[u].x;
+      acc += qd[t + 1] * (double)v[u].y;
+      acc += qd[t + 2] * (double)v[u].z;
+      acc += qd[t + 3] * (double)v[u].w;
+    }
   }
   return (float)acc;
 }
@@ -141,15 +193,77 @@ __device__ __forceinline__ void wave_compact(const unsigned char* flag, int coun
   }
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads) void lf_select_kernel(SelectArgs a) {
-  __shared__ double qd[D];
-  __shared__ float fscore[LF_MAX_CAND_FRAMES];
-  __shared__ unsigned char fflag[LF_MAX_HIST_FRAMES];
-  __shared__ int flist[LF_MAX_CAND_BLOCKS];
-  __shared__ float skey[LF_MAX_CAND_BLOCKS];
-  __shared__ int spos[LF_MAX_CAND_BLOCKS];
-  __shared__ unsigned char sel[LF_MAX_CAND_BLOCKS];
+// Bitonic sort of 256*E (score, position) pairs held E per thread, element e of thread t
+// being index e*256 + t, into ranks_before order along the index.  Partners at distance
+// < 64 are reached with lane shuffles, at distance 64 and 128 through the LDS arrays xs/xp
+// (one barrier pair per such step), at distance >= 256 inside the thread.
+template <int E>
+__device__ __forceinline__ void bitonic_sort(float (&s)[E], int (&p)[E], float* xs, int* xp) {
+  const int tid = threadIdx.x;
+#pragma unroll 1
+  for (int k = 2; k <= kThreads * E; k <<= 1) {
+#pragma unroll 1
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      if (j >= kThreads) {
+        const int de = j / kThreads;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          if ((e & de) == 0 && (e | de) < E) {
+            const int e2 = e | de, i = e * kThreads + tid;
+            const bool up = (i & k) == 0;
+            const bool first_is_lo = ranks_before(s[e], p[e], s[e2], p[e2]);
+            if (first_is_lo != up) {
+              const float ts = s[e]; s[e] = s[e2]; s[e2] = ts;
+              const int tp = p[e]; p[e] = p[e2]; p[e2] = tp;
+            }
+          }
+        }
+      } else {
+        float os[E];
+        int op[E];
+        if (j >= 64) {
+          __syncthreads();
+#pragma unroll
+          for (int e = 0; e < E; ++e) { xs[e * kThreads + tid] = s[e]; xp[e * kThreads + tid] = p[e]; }
+          __syncthreads();
+#pragma unroll
+          for (int e = 0; e < E; ++e) { os[e] = xs[e * kThreads + (tid ^ j)]; op[e] = xp[e * kThreads + (tid ^ j)]; }
+        } else {
+#pragma unroll
+          for (int e = 0; e < E; ++e) { os[e] = __shfl_xor(s[e], j); op[e] = __shfl_xor(p[e], j); }
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int i = e * kThreads + tid;
+          const bool want_first = ((i & j) == 0) == ((i & k) == 0);
+          const bool mine_first = ranks_before(s[e], p[e], os[e], op[e]);
+          const bool other_first = ranks_before(os[e], op[e], s[e], p[e]);
+          if (want_first ? other_first : mine_first) { s[e] = os[e]; p[e] = op[e]; }
+        }
+      }
+    }
+  }
+}
+
+// 64-bit key whose unsigned order is the ranks_before order: larger score first (float32
+// bits made monotonic; -0.0 folded onto +0.0 so the two tie), then lower position.
+__device__ __forceinline__ unsigned long long rank_key(float score, int pos) {
+  uint32_t u = __float_as_uint(score + 0.0f);
+  u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+  return ((unsigned long long)u << 32) | (uint32_t)(0x7fffffff - pos);
+}
+
+template <int D, int E>
+__global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(SelectArgs a) {
+  // LDS carved from one dynamic allocation sized for this call (see select_lds_bytes()).
+  extern __shared__ double lds_raw[];
+  double* qd = lds_raw;                                         // [D]
+  float* xs = reinterpret_cast<float*>(qd + D);                 // [256*E]
+  int* xp = reinterpret_cast<int*>(xs + kThreads * E);          // [256*E]
+  float* fscore = reinterpret_cast<float*>(xp + kThreads * E);  // [m]
+  int* flist = reinterpret_cast<int*>(fscore + a.m);            // [n_tf + f]
+  unsigned char* fflag = reinterpret_cast<unsigned char*>(flist + a.n_tf + a.f);  // [F_h]
+  unsigned char* sel = fflag + ((a.F_h + 3) & ~3);              // [n_cand]
 
   const int tid = threadIdx.x;
   const int h = blockIdx.x / a.n_q, r = blockIdx.x % a.n_q;
@@ -160,8 +274,8 @@ __global__ __launch_bounds__(kThreads) void lf_select_kernel(SelectArgs a) {
   // Eq. 8: frame-level scores against the candidate frames M = [n_sink, F_h - n_win).
   const bool retrieve = a.k_frames < a.m;
   if (retrieve) {
-    for (int c = tid; c < a.m; c += kThreads)
-      fscore[c] = dot_seq<D>(qd, a.kh + ((int64_t)h * a.m + c) * D);
+    const float4* khh = reinterpret_cast<const float4*>(a.kh + (int64_t)h * a.m * D);
+    for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh + c, a.m);
   }
   __syncthreads();
 
@@ -179,49 +293,54 @@ __global__ __launch_bounds__(kThreads) void lf_select_kernel(SelectArgs a) {
   }
   __syncthreads();
   if (tid < 64) wave_compact(fflag, a.F_h, [&](int pos, int i) { flist[pos] = i; });
-  const int n_tf = a.n_sink + a.n_win + a.k_frames;
   if (!a.current_mandatory)
-    for (int t = tid; t < a.f; t += kThreads) flist[n_tf + t] = a.F_h + t;
+    for (int t = tid; t < a.f; t += kThreads) flist[a.n_tf + t] = a.F_h + t;
   __syncthreads();
 
-  // Eq. 10: block-level scores over B_r, candidates in ascending block id.
-  for (int i = tid; i < a.n_cand_pow2; i += kThreads) {
-    float sc = -INFINITY;
-    int pos = 0x7fffffff;
-    if (i < a.n_cand) {
-      const int c = flist[i / a.nb] * a.nb + i % a.nb;
-      sc = dot_seq<D>(qd, a.kt + ((int64_t)h * a.n_k + c) * D);
-      pos = i;
-    }
-    skey[i] = sc;
-    spos[i] = pos;
-    if (i < a.n_cand) sel[i] = 0;
-  }
-  __syncthreads();
-
-  // Eq. 11: top-k blocks.  Bitonic sort of (score, position) so that ranks_before holds
-  // along the array; the first k_blocks entries are J_r.
-  if (a.k_blocks < a.n_cand) {
-    for (int k = 2; k <= a.n_cand_pow2; k <<= 1) {
-      for (int j = k >> 1; j > 0; j >>= 1) {
-        for (int i = tid; i < a.n_cand_pow2; i += kThreads) {
-          const int p = i ^ j;
-          if (p > i) {
-            const float s0 = skey[i], s1 = skey[p];
-            const int p0 = spos[i], p1 = spos[p];
-            const bool first_half = (i & k) == 0;
-            const bool swap = first_half ? ranks_before(s1, p1, s0, p0) : ranks_before(s0, p0, s1, p1);
-            if (swap) {
-              skey[i] = s1; skey[p] = s0;
-              spos[i] = p1; spos[p] = p0;
-            }
-          }
-        }
-        __syncthreads();
+  // Eq. 10: block-level scores over B_r, candidates in ascending block id; candidate
+  // e*256 + tid is element e of this thread.
+  float s[E];
+  int p[E];
+  {
+    const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.n_k * D);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int i = e * kThreads + tid;
+      s[e] = -INFINITY;
+      p[e] = 0x7fffffff;
+      if (i < a.n_cand) {
+        const int c = flist[i / a.nb] * a.nb + i % a.nb;
+        s[e] = dot_quad_major<D>(qd, kth + c, a.n_k);
+        p[e] = i;
+        sel[i] = 0;
       }
     }
-    for (int i = tid; i < a.k_blocks; i += kThreads) sel[spos[i]] = 1;
+  }
+
+  // Eq. 11: top-k blocks, J_r = the candidates of rank < k_blocks.  With at most one
+  // candidate per thread the rank is counted directly (how many keys are larger, keys read
+  // as LDS broadcasts); larger candidate sets are sorted, after which index = rank.
+  if (a.k_blocks < a.n_cand && E == 1) {
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(xs);   // [256], 8-byte aligned
+    const unsigned long long mine = rank_key(s[0], p[0]);
+    keys[tid] = mine;
+    __syncthreads();
+    int rank = 0;
+    const int n2 = (a.n_cand + 1) & ~1;   // keys[n_cand] is a pad (smallest key) when n_cand is odd
+    for (int j = 0; j < n2; j += 2) {
+      const ulonglong2 kk = *reinterpret_cast<const ulonglong2*>(keys + j);
+      rank += kk.x > mine ? 1 : 0;
+      rank += kk.y > mine ? 1 : 0;
+    }
+    if (tid < a.n_cand && rank < a.k_blocks) sel[tid] = 1;
+  } else if (a.k_blocks < a.n_cand) {
+    bitonic_sort<E>(s, p, xs, xp);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (e * kThreads + tid < a.k_blocks) sel[p[e]] = 1;
   } else {
+    __syncthreads();
     for (int i = tid; i < a.n_cand; i += kThreads) sel[i] = 1;
   }
   __syncthreads();
@@ -287,13 +406,21 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
   sa.current_mandatory = b->current_mandatory;
   sa.list_len = b->list_len;
   sa.n_cand = dm->n_cand;
-  int p2 = 1;
-  while (p2 < dm->n_cand) p2 <<= 1;
-  sa.n_cand_pow2 = p2;
+  sa.n_tf = dm->n_tf;
+  // E = candidate pairs per thread in the sort: 256*E >= n_cand, E a power of two
+  int e = 1;
+  while (kThreads * e < dm->n_cand) e <<= 1;
   const unsigned sel_grid = (unsigned)(dm->H * dm->n_q);
-  if (dm->d == 128)
-    hipLaunchKernelGGL(lf_select_kernel<128>, dim3(sel_grid), dim3(kThreads), 0, st, sa);
-  else
-    hipLaunchKernelGGL(lf_select_kernel<64>, dim3(sel_grid), dim3(kThreads), 0, st, sa);
+  const size_t lds = select_lds_bytes(sa, e);
+#define LF_LAUNCH_SELECT(DD, EE) \
+  hipLaunchKernelGGL((lf_select_kernel<DD, EE>), dim3(sel_grid), dim3(kThreads), lds, st, sa)
+  if (dm->d == 128) {
+    if (e == 1) LF_LAUNCH_SELECT(128, 1); else if (e == 2) LF_LAUNCH_SELECT(128, 2);
+    else if (e == 4) LF_LAUNCH_SELECT(128, 4); else LF_LAUNCH_SELECT(128, 8);
+  } else {
+    if (e == 1) LF_LAUNCH_SELECT(64, 1); else if (e == 2) LF_LAUNCH_SELECT(64, 2);
+    else if (e == 4) LF_LAUNCH_SELECT(64, 4); else LF_LAUNCH_SELECT(64, 8);
+  }
+#undef LF_LAUNCH_SELECT
   return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
 }

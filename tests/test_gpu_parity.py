@@ -52,7 +52,12 @@ def _run_select(torch, lf, w, x, check_intermediates=True):
                              ("k_hat", off[2], I["k_hat"].shape[1] if ob.k_frames < len(I["M"]) else 0)):
             if cnt == 0:
                 continue
-            got = raw[o:o + H * cnt * d * 4].view(np.float32).reshape(H, cnt, d)
+            got = raw[o:o + H * cnt * d * 4].view(np.float32)
+            if name == "q_tilde":
+                got = got.reshape(H, cnt, d)
+            else:   # channel-quad major: [H][d/4][rows][4]
+                got = got.reshape(H, d // 4, cnt, 4).transpose(0, 2, 1, 3).reshape(H, cnt, d)
+            got = np.ascontiguousarray(got)
             assert np.array_equal(got.view(np.uint32), I[name].view(np.uint32)), name
     got = idx.cpu().numpy()
     assert got.shape == want.shape and got.dtype == np.int32
@@ -110,6 +115,17 @@ SMALL = {
     "short_frame": lambda: synth.small_ragged(frame_len=40, chunk_idx=5, heads=2, k_frames=1),
     "many_frames": lambda: synth.small_ragged(frame_len=64, chunk_idx=40, frames_per_chunk=2,
                                               heads=1, k_frames=5, n_sink=2, n_win=3),
+    # candidate sets wider than one per thread: 320, 560 and 1040 candidate blocks
+    "wide_320": lambda: synth.small_ragged(frame_len=500, chunk_idx=28, frames_per_chunk=5, heads=1,
+                                           k_frames=35, n_sink=2, n_win=3,
+                                           ratio_of=synth.OF_CANDIDATES, keep_fixed=0.5),
+    "wide_560": lambda: synth.small_ragged(frame_len=500, chunk_idx=28, frames_per_chunk=5, heads=1,
+                                           k_frames=65, n_sink=2, n_win=3,
+                                           ratio_of=synth.OF_CANDIDATES, keep_fixed=0.3),
+    "wide_1040_compete": lambda: synth.small_ragged(frame_len=500, chunk_idx=28, frames_per_chunk=5,
+                                                    heads=1, k_frames=120, n_sink=2, n_win=3,
+                                                    current_mandatory=0,
+                                                    ratio_of=synth.OF_CANDIDATES, keep_fixed=0.1),
 }
 
 
