@@ -29,9 +29,14 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
-# copy kernel of known size); see profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch in bytes, measured offline with rocprofv3 --pmc (FETCH_SIZE then
+# WRITE_SIZE, KiB per dispatch; FETCH_SIZE scaled by 1.994, the factor a plain 256 MiB copy in
+# the same run shows, WRITE_SIZE by 1.000): profiles/last_chunk_pmc_counters.txt.
+# None for workloads that were not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("last_chunk", "attn"): (242500 * 1.994 + 14040) * 1024,
+    ("last_chunk", "select"): ((56190 + 1454 + 8668) * 1.994 + (6752 + 180 + 675)) * 1024,
+}
 
 
 def _workloads():
@@ -103,6 +108,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="last_chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE scaling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (heads would shard across GPUs "
@@ -132,6 +140,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # one copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
