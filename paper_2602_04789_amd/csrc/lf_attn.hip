@@ -40,7 +40,6 @@ struct AttnArgs {
   int64_t v_stride_tok, v_stride_head, o_stride_tok, o_stride_head;
   int n, nb, n_q, n_k, list_len;
   int total_wg, wg_per_xcd;
-  int k_extent, v_extent;  // bytes of one head's K / V, first to last element
   float c;  // softmax_scale * log2(e)
 };
 
@@ -58,11 +57,12 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 
 // 16-byte chunk swizzles of the LDS tiles (row = token within the tile, ch = 8-channel chunk).
 // K is read row-wise, 16 bytes per lane, 16 consecutive rows at one logical chunk: XOR with
-// the row spreads them over all banks.  V is read with the transposing 8-byte LDS read, four
-// consecutive rows x 64 bytes at a time: XOR moves each of the four rows to its own 64 bytes.
+// the row spreads them over all banks.  V is read with the transposing 8-byte LDS read, which
+// takes 32 bytes from each of four consecutive rows per group of 16 lanes; of the XOR
+// patterns measured, shifting each of eight consecutive rows by two chunks was the fastest.
 template <int CH> __device__ __forceinline__ int k_swz(int row, int ch) { return ch ^ (row & (CH - 1)); }
 template <int CH> __device__ __forceinline__ int v_swz(int row, int ch) {
-  return ch ^ ((row & (CH / 4 - 1)) << 2);
+  return CH == 16 ? ch ^ ((row & 7) << 1) : ch ^ ((row & 1) << 2);
 }
 
 // Workgroup barrier that orders LDS accesses only; the global->LDS loads are waited for
@@ -121,9 +121,8 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 
   // Tile load, global -> LDS without passing through registers: load instruction i of
   // wavefront `wave` fills tile rows [RPI*(LPW*wave+i), +RPI); lane l lands at byte 16*l
-  // of that 1 KiB stripe, so it fetches the chunk the swizzle assigns to that place.  Rows
-  // past the block's token count re-read its last token (finite data that the mask removes).
-  // Per-lane byte offsets inside a full tile are loop invariants.
+  // of that 1 KiB stripe, so it fetches the chunk the swizzle assigns to that place.
+  // Per-lane byte offsets inside a tile are loop invariants.
   const int ld_r = lane / CH, ld_p = lane % CH;
   uint32_t koff[LPW], voff[LPW];
 #pragma unroll
@@ -137,48 +136,38 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     const int2 e = ent[t & (kMaxEnt - 1)];
     return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
   };
-  // The loads are buffer loads (resource = this head's K or V, scalar offset = the tile's
-  // first token, vector offset = the lane's place in the tile): no per-load address math.
-  // They are issued from inline assembly, a few at a time between the compute phases of the
-  // current tile, so that the vector-memory queue never backs up into the issuing wavefront.
-  auto make_rsrc = [](const char* base, int bytes) {
+  // The loads are raw buffer loads whose resource is the tile itself: base = the block's
+  // first token, num_records = its token count x the row pitch.  Rows past a short block's
+  // count are then out of range, which touches no memory and writes zeros, so the loads need
+  // no per-lane address arithmetic and no branch.  They are issued from inline assembly, a
+  // few at a time between the compute phases, so that the vector-memory queue never backs up
+  // into the issuing wavefront.
+  auto tile_rsrc = [](const char* base, uint32_t row_bytes, int2 e) {
     int32x4 r;
-    const uint64_t b = (uint64_t)base;
-    r[0] = (int)(uint32_t)b;
-    r[1] = (int)(uint32_t)(b >> 32);  // stride 0: raw buffer
-    r[2] = bytes;
+    const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)e.x * row_bytes;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));  // stride 0: raw buffer
+    r[2] = __builtin_amdgcn_readfirstlane((int)((uint32_t)e.y * row_bytes));
     r[3] = 0x00020000;
     return r;
   };
-  const int32x4 krs = make_rsrc(Kh, a.k_extent), vrs = make_rsrc(Vh, a.v_extent);
-  auto dma16 = [](int32x4 rs, uint32_t lds_addr, uint32_t voff, uint32_t soff) __attribute__((always_inline)) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rs), "s"(soff));
+  auto dma16 = [](int32x4 rs, uint32_t lds_addr, uint32_t voff) __attribute__((always_inline)) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rs));
   };
   // Loads i0 .. i1-1 (of LPW) of this wavefront's share of one tile.
-  auto fetch_part = [&](int2 e, uint4* dst, int32x4 rs, uint32_t row_bytes, const uint32_t (&off)[LPW],
-                        bool is_k, int i0, int i1) __attribute__((always_inline)) {
-    const uint32_t base = (uint32_t)e.x * row_bytes;
+  auto fetch_part = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW], int i0, int i1)
+      __attribute__((always_inline)) {
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
-    if (e.y == 64) {
 #pragma unroll
-      for (int i = i0; i < i1; ++i) dma16(rs, lds0 + i * 1024, off[i], base);
-    } else {
-      const int last = max(e.y - 1, 0);
-#pragma unroll
-      for (int i = i0; i < i1; ++i) {
-        const int row = RPI * (LPW * wave + i) + ld_r;
-        const uint32_t swz = (uint32_t)(is_k ? k_swz<CH>(row, ld_p) : v_swz<CH>(row, ld_p)) * 16u;
-        dma16(rs, lds0 + i * 1024, (uint32_t)min(row, last) * row_bytes + swz, base);
-      }
-    }
+    for (int i = i0; i < i1; ++i) dma16(rs, lds0 + i * 1024, off[i]);
   };
   auto fetch_k = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(e, buf, krs, (uint32_t)k_row_bytes, koff, true, i0, i1);
+    fetch_part(tile_rsrc(Kh, (uint32_t)k_row_bytes, e), buf, koff, i0, i1);
   };
   auto fetch_v = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(e, buf + TILE, vrs, (uint32_t)v_row_bytes, voff, false, i0, i1);
+    fetch_part(tile_rsrc(Vh, (uint32_t)v_row_bytes, e), buf + TILE, voff, i0, i1);
   };
 
   // LDS addresses of this lane's operand fragments inside a tile (loop invariants).
@@ -229,33 +218,39 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
     }
     __syncthreads();
-    int2 e_cur = entry(t0);
-    fetch_k(e_cur, buf0, 0, LPW);
-    fetch_v(e_cur, buf0, 0, LPW);
-    int2 e_next = entry(min(t0 + 1, t1 - 1));
+    // Software pipeline, one tile deep: iteration t computes S^T of tile t+1 (matrix core)
+    // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
+    // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
+    int2 e0 = entry(t0), e1 = entry(min(t0 + 1, t1 - 1)), e2 = entry(min(t0 + 2, t1 - 1));
+    fetch_k(e0, buf0, 0, LPW);
+    fetch_v(e0, buf0, 0, LPW);
+    fetch_k(e1, buf1, 0, LPW);
 
-    // One tile: wait for it, then compute it while the next tile's loads are issued, in four
-    // slots, into the other buffer.
-    auto tile = [&](int t, const uint4* cur, uint4* other) __attribute__((always_inline)) {
-      const int cnt = e_cur.y;
-      const bool more = t + 1 < t1;
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of tile t has landed
-      lds_barrier();                             // ... everyone's has; `other` is no longer read
-      if (more) fetch_k(e_next, other, 0, H1);
+    // S^T[kv, q] of this wavefront's 32 KV rows x 32 query rows, from the K tile in `kt`.
+    auto s_half = [&](const uint4* kt, f32x16 acc, int s0) __attribute__((always_inline)) {
+      Frag kf[KS / 2];
+#pragma unroll
+      for (int s = 0; s < KS / 2; ++s) kf[s].u = kt[kaddr[s0 + s]];
+#pragma unroll
+      for (int s = 0; s < KS / 2; ++s)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[s0 + s].v, acc, 0, 0, 0);
+      return acc;
+    };
+    f32x16 zero16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
-      // S^T[kv, q] for this wavefront's 32 KV rows x 32 query rows.
-      f32x16 sacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
-      {
-        Frag kf[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kf[s].u = cur[kaddr[s]];
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[s].v, sacc, 0, 0, 0);
-      }
-      if (more) fetch_k(e_next, other, H1, LPW);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    lds_barrier();
+    f32x16 sacc = s_half(buf0, s_half(buf0, zero16, 0), KS / 2);
+
+    // Past the end of the list the pipeline runs on the last entry again: its loads and its
+    // S^T are redundant and unused, which keeps the loop body free of branches.
+    auto tile = [&](int t, uint4* cur, uint4* other) __attribute__((always_inline)) {
+      const int cnt = e0.y;
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of K_{t+1}, V_t has landed
+      lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
+      fetch_k(e2, cur, 0, H1);
       // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
       if (cnt < 64) {
 #pragma unroll
@@ -264,6 +259,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           if (kv >= cnt) sacc[i] = -INFINITY;
         }
       }
+      f32x16 snext = s_half(other, zero16, 0);
       float mx = fmaxf(fmaxf(sacc[0], sacc[1]), fmaxf(sacc[2], sacc[3]));
 #pragma unroll
       for (int i = 4; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sacc[i], sacc[i + 1]));
@@ -273,6 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
       }
       const float m_new = fmaxf(m_run, mx * a.c);
+      fetch_k(e2, cur, H1, LPW);
       if (__ballot(m_new > m_run) != 0ull) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
@@ -282,7 +279,8 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
         m_run = m_new;
       }
-      if (more) fetch_v(e_next, other, 0, H1);
+      fetch_v(e1, other, 0, H1);
+      snext = s_half(other, snext, KS / 2);
 
       float p[16];
 #pragma unroll
@@ -304,11 +302,13 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
         }
       }
-      if (more) fetch_v(e_next, other, H1, LPW);
+      fetch_v(e1, other, H1, LPW);
       l_run += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])) +
                (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
-      e_cur = e_next;
-      e_next = entry(min(t + 2, t1 - 1));
+      sacc = snext;
+      e0 = e1;
+      e1 = e2;
+      e2 = entry(min(t + 3, t1 - 1));
     };
     for (int t = t0; t < t1; t += 2) {
       tile(t, buf0, buf1);
@@ -385,8 +385,6 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
   a.total_wg = dm->H * dm->n_q;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   a.c = scale * 1.4426950408889634f;
-  a.k_extent = (int)(((int64_t)s->kv_len - 1) * s->k_stride_tok * 2 + dm->d * 2);
-  a.v_extent = (int)(((int64_t)s->kv_len - 1) * s->v_stride_tok * 2 + dm->d * 2);
   const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
   hipStream_t st = (hipStream_t)stream;
   if (dm->d == 128)
