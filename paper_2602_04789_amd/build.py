@@ -23,9 +23,14 @@ SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          # keep MFMA accumulators in ordinary VGPRs (the attention kernel runs one wavefront
-          # per SIMD; the AGPR form costs copies around every vector-ALU use)
+          # keep MFMA accumulators in ordinary VGPRs (the attention kernel's softmax reads
+          # them with vector-ALU instructions; the AGPR form costs a copy around every use)
           "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+# Per-file additions.  The attention kernel produces no NaN from finite inputs (its masks
+# are -inf and its running maximum starts finite), so max() there need not quiet signalling
+# NaNs first: that drops one vector instruction per score.  The selection kernels keep the
+# default: their comparisons define the bit-exact index lists.
+PER_FILE = {"lf_attn.hip": ["-fno-honor-nans"]}
 
 
 def _hipcc() -> str:
@@ -51,7 +56,8 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
         path = os.path.join(CSRC, src)
         obj = os.path.join(OBJ, src.replace(".", "_") + ".o")
         if src.endswith(".hip"):
-            cmd = [hipcc, "-c", path, "-o", obj] + COMMON + DEVICE + list(extra_device_flags)
+            cmd = ([hipcc, "-c", path, "-o", obj] + COMMON + DEVICE + PER_FILE.get(src, []) +
+                   list(extra_device_flags))
         else:
             cmd = [hipcc, "-x", "c++", "-c", path, "-o", obj, "-ffp-contract=off"] + COMMON
         out = _run(cmd)

@@ -24,6 +24,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int int32x4 __attribute__((ext_vector_type(4)));
 
@@ -151,9 +152,9 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     r[3] = 0x00020000;
     return r;
   };
-  auto dma16 = [](int32x4 rs, uint32_t lds_addr, uint32_t voff) __attribute__((always_inline)) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rs));
+  auto dma16 = [](int32x4 rs, uint32_t lds_addr, int lds_add, uint32_t voff) __attribute__((always_inline)) {
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rs), "i"(lds_add) : "scc");
   };
   // Loads i0 .. i1-1 (of LPW) of this wavefront's share of one tile.
   auto fetch_part = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW], int i0, int i1)
@@ -161,13 +162,15 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
 #pragma unroll
-    for (int i = i0; i < i1; ++i) dma16(rs, lds0 + i * 1024, off[i]);
+    for (int i = i0; i < i1; ++i) dma16(rs, lds0, i * 1024, off[i]);
   };
-  auto fetch_k = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(tile_rsrc(Kh, (uint32_t)k_row_bytes, e), buf, koff, i0, i1);
+  auto k_rsrc = [&](int2 e) { return tile_rsrc(Kh, (uint32_t)k_row_bytes, e); };
+  auto v_rsrc = [&](int2 e) { return tile_rsrc(Vh, (uint32_t)v_row_bytes, e); };
+  auto fetch_k = [&](int32x4 rs, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
+    fetch_part(rs, buf, koff, i0, i1);
   };
-  auto fetch_v = [&](int2 e, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(tile_rsrc(Vh, (uint32_t)v_row_bytes, e), buf + TILE, voff, i0, i1);
+  auto fetch_v = [&](int32x4 rs, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
+    fetch_part(rs, buf + TILE, voff, i0, i1);
   };
 
   // LDS addresses of this lane's operand fragments inside a tile (loop invariants).
@@ -222,9 +225,9 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
     int2 e0 = entry(t0), e1 = entry(min(t0 + 1, t1 - 1)), e2 = entry(min(t0 + 2, t1 - 1));
-    fetch_k(e0, buf0, 0, LPW);
-    fetch_v(e0, buf0, 0, LPW);
-    fetch_k(e1, buf1, 0, LPW);
+    fetch_k(k_rsrc(e0), buf0, 0, LPW);
+    fetch_v(v_rsrc(e0), buf0, 0, LPW);
+    fetch_k(k_rsrc(e1), buf1, 0, LPW);
 
     // S^T[kv, q] of this wavefront's 32 KV rows x 32 query rows, from the K tile in `kt`.
     auto s_half = [&](const uint4* kt, f32x16 acc, int s0) __attribute__((always_inline)) {
@@ -250,7 +253,8 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       const int cnt = e0.y;
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of K_{t+1}, V_t has landed
       lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
-      fetch_k(e2, cur, 0, H1);
+      const int32x4 krs = k_rsrc(e2), vrs = v_rsrc(e1);
+      fetch_k(krs, cur, 0, H1);
       // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
       if (cnt < 64) {
 #pragma unroll
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
       }
       const float m_new = fmaxf(m_run, mx * a.c);
-      fetch_k(e2, cur, H1, LPW);
+      fetch_k(krs, cur, H1, LPW);
       if (__ballot(m_new > m_run) != 0ull) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
         m_run = m_new;
       }
-      fetch_v(e1, other, 0, H1);
+      fetch_v(vrs, other, 0, H1);
       snext = s_half(other, snext, KS / 2);
 
       float p[16];
@@ -294,6 +298,13 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[8 * u + e];
+        // row sums of P as rounded for the product, two values per instruction
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          const bf16x2 pr = {pf[e], pf[e + 1]};
+          const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
+        }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
           const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr[u][0][mb]));
@@ -302,9 +313,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
         }
       }
-      fetch_v(e1, other, H1, LPW);
-      l_run += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7])) +
-               (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
+      fetch_v(vrs, other, H1, LPW);
       sacc = snext;
       e0 = e1;
       e1 = e2;
