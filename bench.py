@@ -6,12 +6,16 @@ lf_chunk_budget (host) -> lf_select_mask -> lf_sparse_attn.  Prints ONE JSON lin
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload last_chunk]
 
+    python bench.py --workload rollout     # 7 chunks x 4 steps, 40 heads: 28 calls per step
+
 value        effective TFLOP/s on kept blocks over the whole step (select + attention):
              4 d sum_{kept (r,c)} rows_r cols_c valid-token FLOPs / wall time per step.
 roofline     dominant kernel (block-sparse attention, bf16 MFMA): the same FLOPs over the
              kernel's own duration, HIP events on the launch stream inside the timed region.
 select       mask selection as an HBM-bound stage: one read of Q and K (bf16) per call.
 cpu_baseline the numpy oracle on the host cores, on a bounded sample of the same workload.
+measured     what this GPU reaches on a library bf16 GEMM and on a streaming copy (context for
+             the published peaks the roofline fractions are taken against).
 """
 from __future__ import annotations
 
@@ -34,7 +38,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # the same run shows, WRITE_SIZE by 1.000): profiles/last_chunk_pmc_counters.txt.
 # None for workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("last_chunk", "attn"): (242500 * 1.994 + 14040) * 1024,
+    ("last_chunk", "attn"): (254600 * 1.994 + 14040) * 1024,
     ("last_chunk", "select"): ((56190 + 1454 + 8668) * 1.994 + (6752 + 180 + 675)) * 1024,
 }
 
@@ -42,7 +46,10 @@ MEASURED_TRAFFIC_BYTES = {
 def _workloads():
     from paper_2602_04789_amd import synth
     return {"first_chunk": synth.cfg_first_chunk, "mid_rollout": synth.cfg_mid_rollout,
-            "last_chunk": synth.cfg_last_chunk, "tiny": synth.cfg_tiny}
+            "last_chunk": synth.cfg_last_chunk, "tiny": synth.cfg_tiny,
+            # the paper's own operating point (1536 tokens per frame, Chunk-Aware Growth,
+            # current chunk competing) at its fourth and its last chunk
+            "paper5s_mid": lambda: synth.cfg_paper_5s(4), "paper5s_last": lambda: synth.cfg_paper_5s(7)}
 
 
 def kept_flops(lists: np.ndarray, w) -> float:
@@ -101,6 +108,100 @@ def cpu_baseline(w, x, lists_gpu, out_gpu, budget_s: float = 15.0):
     }
 
 
+def measured_peaks(torch):
+    """Library bf16 GEMM rate and streaming-copy rate on this GPU, for context."""
+    n = 8192
+    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        torch.matmul(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    gemm = 10 * 2.0 * n ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    del a, b
+    x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    y = torch.empty_like(x)
+    for _ in range(2):
+        y.copy_(x)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        y.copy_(x)
+    e1.record()
+    torch.cuda.synchronize()
+    stream = 10 * 2.0 * float(1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9   # read + write
+    del x, y
+    return {"gemm_bf16_8192_tflops": gemm, "stream_copy_1gib_read_plus_write_gbps": stream}
+
+
+def run_rollout(args, torch, lf, synth):
+    """One step = the 28 calls of a 7-chunk, 4-denoising-step rollout at 40 heads: the cache
+    grows by one chunk per chunk index, the keep ratio follows the schedule, history K/V stay
+    fixed over the four steps of a chunk and the current chunk is redrawn per step."""
+    calls = []
+    total_flops = 0.0
+    for chunk in range(1, 8):
+        for step_i in range(4):
+            w = synth.cfg_rollout(chunk, step_i)
+            x = synth.make_inputs(w)
+            Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
+            sched = lf.make_schedule(w.schedule)
+            b = lf.lf_chunk_budget(w.chunk_idx, sched)
+            sh = lf.make_shape(Q, K, frame_len=w.frame_len, block=w.block)
+            ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+            idx = torch.empty((w.heads, w.frames_per_chunk * w.blocks_per_frame, b.list_len),
+                              dtype=torch.int32, device="cuda")
+            out = torch.empty_like(Q)
+            calls.append((w, sched, Q, K, V, b, ws, idx, out))
+
+    def step():
+        for (w, sched, Q, K, V, b, ws, idx, out) in calls:
+            bb = lf.lf_chunk_budget(w.chunk_idx, sched)
+            lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
+            lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_chunk = []
+    for (w, sched, Q, K, V, b, ws, idx, out) in calls:
+        total_flops += kept_flops(idx.cpu().numpy(), w)
+    # per-chunk times: the four steps of each chunk, timed on their own
+    for c in range(7):
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for (w, sched, Q, K, V, b, ws, idx, out) in calls[4 * c:4 * c + 4]:
+            bb = lf.lf_chunk_budget(w.chunk_idx, sched)
+            lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
+            lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+        torch.cuda.synchronize()
+        per_chunk.append((time.perf_counter() - t1) * 1e3)
+    ms_step = wall * 1e3 / args.steps
+    w0 = calls[0][0]
+    print(json.dumps({
+        "metric": "effective TFLOP/s on kept blocks, whole step (mask selection + block-sparse attention)",
+        "value": total_flops / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"rollout: {w0.heads} heads x {w0.head_dim}, 7 chunks x 4 steps = 28 calls, "
+                               f"Q {w0.q_len}, KV {w0.q_len}..{calls[-1][0].kv_len}, keep ratio by the linear schedule",
+                   "heads": w0.heads, "head_dim": w0.head_dim, "calls": len(calls),
+                   "list_len_per_chunk": [int(calls[4 * c][5].list_len) for c in range(7)]},
+        "ms_per_chunk_4_steps": per_chunk, "kept_gflop": total_flops / 1e9,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +209,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="last_chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the library GEMM / streaming read measurements")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time one step right after streaming a 1 GiB buffer through the caches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -121,6 +226,10 @@ def main():
     lf.load()   # raises if the HIP library is not built: there is no fallback path
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.workload == "rollout":
+        if args.steps == 100 and args.warmup == 20:   # the defaults are sized for one chunk
+            args.steps, args.warmup = 5, 1
+        return run_rollout(args, torch, lf, synth)
     w = _workloads()[args.workload]()
     x = synth.make_inputs(w)
     Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
@@ -162,8 +271,23 @@ def main():
     wall = time.perf_counter() - t0
 
     ms_step = wall * 1e3 / args.steps
-    sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    attn_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    sel_all = np.array([e[0].elapsed_time(e[1]) for e in ev])
+    attn_all = np.array([e[1].elapsed_time(e[2]) for e in ev])
+    sel_ms, attn_ms = float(sel_all.mean()), float(attn_all.mean())
+    cold = None
+    if args.cold:
+        big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        big.fill_(3)                 # 1 GiB through L2 and the memory-side cache
+        torch.cuda.synchronize()
+        c = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        c[0].record()
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, b, indices=idx, workspace=ws)
+        c[1].record()
+        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+        c[2].record()
+        torch.cuda.synchronize()
+        cold = {"select_ms": c[0].elapsed_time(c[1]), "attn_ms": c[1].elapsed_time(c[2])}
+        del big
     lists = idx.cpu().numpy()
     flops = kept_flops(lists, w)
     tile_flops = 4.0 * 64 * 64 * w.head_dim * lists.size
@@ -185,6 +309,8 @@ def main():
                    "heads": w.heads, "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len,
                    "list_len": int(b.list_len), "k_blocks": int(b.k_blocks), "k_frames": int(b.k_frames)},
         "ms_per_chunk": ms_step, "select_ms": sel_ms, "attn_ms": attn_ms,
+        "select_ms_median_min": [float(np.median(sel_all)), float(sel_all.min())],
+        "attn_ms_median_min": [float(np.median(attn_all)), float(attn_all.min())],
         "kept_gflop": flops / 1e9, "tile_gflop": tile_flops / 1e9,
         "roofline": {"kernel": "lf_attn_kernel", "bound": "mfma", "achieved": attn_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
@@ -193,6 +319,10 @@ def main():
                    "frac": sel_gbps / PEAK_HBM_GBPS, "bytes": sel_bytes,
                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "select"))},
     }
+    if cold is not None:
+        res["cold_after_1gib_stream"] = cold
+    if not args.no_measured_peaks:
+        res["measured"] = measured_peaks(torch)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, x, lists, out.float().cpu().numpy().astype(np.float64))
     print(json.dumps(res))
