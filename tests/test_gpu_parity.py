@@ -192,6 +192,9 @@ def test_attention_list_edge_cases(gpu):
         "unordered": np.tile(np.array([n_k - 1, 0, 5, 2], np.int32), (w.heads, n_q, 1)),
         "invalid_ids_skipped": np.tile(np.array([-1, 3, n_k, 1 << 30, 4], np.int32), (w.heads, n_q, 1)),
         "duplicate": np.tile(np.array([2, 2, 7], np.int32), (w.heads, n_q, 1)),
+        # longer than the kernel decodes in one pass (512 entries): three passes, the last short
+        "three_passes": np.tile((np.arange(1100, dtype=np.int32) * 7) % n_k, (w.heads, n_q, 1)),
+        "one_pass_plus_one": np.tile((np.arange(513, dtype=np.int32) * 3) % n_k, (w.heads, n_q, 1)),
     }
     for name, lists in cases.items():
         print("edge case", name, flush=True)
@@ -250,6 +253,9 @@ FULL = {
     "first_chunk": synth.cfg_first_chunk,
     "mid_rollout": synth.cfg_mid_rollout,
     "last_chunk": synth.cfg_last_chunk,
+    # the paper's own operating point (Experimental Details; hyper-parameter table)
+    "paper5s_mid": lambda: synth.cfg_paper_5s(4),
+    "paper5s_last": lambda: synth.cfg_paper_5s(7),
 }
 
 
