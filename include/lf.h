@@ -204,6 +204,45 @@ int lf_sparse_attn(const void* Q, const void* Kcache, const void* Vcache,
                    const lf_shape* shape, const int32_t* indices, int32_t list_len,
                    float softmax_scale, void* O, void* hip_stream);
 
+/*
+ * Pooled-key cache (an extension the paper does not describe; it follows from its setting).
+ * The keys of a finished chunk never change again (Sec. 3: the rollout appends each generated
+ * chunk's K/V to the cache and later chunks only read it), so their block means and frame means
+ * (Eq. 7) need not be recomputed by every call: only Q and the chunk being denoised change
+ * between the calls of a rollout.  The cache holds, for up to max_frames frames,
+ *   k_tilde  float32 [H][d/4][max_frames*nb][4]   block means, row = KV block id
+ *   k_hat    float32 [H][d/4][max_frames][4]      frame means, row = frame id (every frame)
+ * in this order, channel-quad major as in lf_workspace_layout.  The caller owns the memory
+ * (device, 256-byte aligned, >= lf_kcache_bytes()) and keeps it between calls.
+ *
+ * lf_kcache_bytes   bytes for `shape` (heads, head_dim, frame_len, block are read) and
+ *                   max_frames; 0 on bad input.
+ * lf_kcache_update  pools frames [frame_begin, frame_end) of Kcache into the cache, with the
+ *                   arithmetic of lf_select_mask.  0 <= frame_begin <= frame_end <= frames of
+ *                   Kcache (kv_len / frame_len) <= max_frames; an empty range enqueues nothing.
+ * lf_select_mask_cached  lf_select_mask with k_tilde and k_hat taken from the cache.  If
+ *                   Kcache is not NULL, the block means of the current chunk's frames
+ *                   [n_hist_frames, n_hist_frames + frames_per_chunk) are first refreshed from
+ *                   it, in the same launch that pools Q (their frame means are left alone:
+ *                   candidate frames are history frames; lf_kcache_update writes them when the
+ *                   chunk is committed); with Kcache NULL only Q is read.  Returns the same
+ *                   lists as lf_select_mask bit for bit, provided the history frames have been
+ *                   updated from the keys the caller would pass to lf_select_mask (and the
+ *                   current ones too when Kcache is NULL).  workspace: device scratch,
+ *                   256-byte aligned, of >= heads * n_q * head_dim * 4 bytes
+ *                   (lf_workspace_bytes() is enough).
+ * Errors: as lf_select_mask; LF_ERR_SHAPE for a bad frame range or max_frames;
+ *   LF_ERR_WORKSPACE for a cache or workspace that is missing or too small.
+ */
+size_t lf_kcache_bytes(const lf_shape* shape, int32_t max_frames);
+int lf_kcache_update(const void* Kcache, const lf_shape* shape, int32_t frame_begin,
+                     int32_t frame_end, int32_t max_frames, void* kcache, size_t kcache_bytes,
+                     void* hip_stream);
+int lf_select_mask_cached(const void* Q, const void* Kcache, void* kcache, size_t kcache_bytes,
+                          int32_t max_frames, const lf_shape* shape, const lf_budget* budget,
+                          int32_t* indices, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
 /* Static, NUL-terminated description of an lf_status value. */
 const char* lf_strerror(int status);
 

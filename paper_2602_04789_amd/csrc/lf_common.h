@@ -25,6 +25,11 @@ int lf_derive(const lf_shape* s, const lf_budget* b, lf_dims* out);
 // Kernel launchers (defined in the .hip files); return LF_OK or LF_ERR_HIP.
 int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_budget* b,
                      const lf_dims* dm, int32_t* indices, void* workspace, void* stream);
+int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm, int frame0, int frame1,
+                            int max_frames, void* kcache, void* stream);
+int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
+                            const lf_shape* s, const lf_budget* b, const lf_dims* dm, int32_t* indices,
+                            void* workspace, void* stream);
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
                    const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
                    void* O, void* stream);

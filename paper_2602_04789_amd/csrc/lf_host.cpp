@@ -103,6 +103,8 @@ extern "C" int lf_chunk_budget(int32_t chunk_idx, const lf_schedule* s, lf_budge
   return LF_OK;
 }
 
+static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
 int lf_derive(const lf_shape* s, const lf_budget* b, lf_dims* o) {
   if (!s || !o) return LF_ERR_NULL;
   if (s->dtype != LF_BF16) return LF_ERR_DTYPE;
@@ -183,8 +185,6 @@ extern "C" int lf_workspace_layout(const lf_shape* s, const lf_budget* b, size_t
   return LF_OK;
 }
 
-static bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
-
 extern "C" int lf_select_mask(const void* Q, const void* K, const lf_shape* s, const lf_budget* b,
                               int32_t* indices, void* workspace, size_t workspace_bytes,
                               void* stream) {
@@ -196,6 +196,63 @@ extern "C" int lf_select_mask(const void* Q, const void* K, const lf_shape* s, c
   if (!workspace || workspace_bytes < dm.ws_bytes) return LF_ERR_WORKSPACE;
   if (misaligned(workspace, 256)) return LF_ERR_ALIGN;
   return lf_launch_select(Q, K, s, b, &dm, indices, workspace, stream);
+}
+
+// Bytes of the pooled-key cache; 0 when the sizes are unusable.
+static size_t kcache_bytes(const lf_dims& dm, int32_t max_frames) {
+  if (max_frames < 1 || max_frames > LF_MAX_HIST_FRAMES + 64) return 0;
+  const size_t rows = (size_t)max_frames * dm.nb + (size_t)max_frames;
+  return align_up((size_t)dm.H * rows * dm.d * sizeof(float), 256);
+}
+
+extern "C" size_t lf_kcache_bytes(const lf_shape* s, int32_t max_frames) {
+  if (!s) return 0;
+  // only heads, head_dim, frame_len and block matter here: check them on a one-frame shape
+  lf_shape one = *s;
+  one.q_len = one.kv_len = s->frame_len;
+  one.q_stride_tok = one.k_stride_tok = one.v_stride_tok = one.o_stride_tok = 128;
+  one.q_stride_head = one.k_stride_head = one.v_stride_head = one.o_stride_head = 0;
+  lf_dims dm;
+  if (lf_derive(&one, nullptr, &dm) != LF_OK) return 0;
+  return kcache_bytes(dm, max_frames);
+}
+
+extern "C" int lf_kcache_update(const void* K, const lf_shape* s, int32_t frame_begin,
+                                int32_t frame_end, int32_t max_frames, void* kcache,
+                                size_t kcache_bytes_given, void* stream) {
+  if (!K || !s) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, nullptr, &dm);
+  if (rc != LF_OK) return rc;
+  if (frame_begin < 0 || frame_end < frame_begin || frame_end > dm.F || dm.F > max_frames)
+    return LF_ERR_SHAPE;
+  const size_t need = kcache_bytes(dm, max_frames);
+  if (need == 0) return LF_ERR_SHAPE;
+  if (!kcache || kcache_bytes_given < need) return LF_ERR_WORKSPACE;
+  if (misaligned(K, 16) || misaligned(kcache, 256)) return LF_ERR_ALIGN;
+  if (frame_end == frame_begin) return LF_OK;
+  return lf_launch_kcache_update(K, s, &dm, frame_begin, frame_end, max_frames, kcache, stream);
+}
+
+extern "C" int lf_select_mask_cached(const void* Q, const void* Kcache, void* kcache,
+                                     size_t kcache_bytes_given, int32_t max_frames,
+                                     const lf_shape* s, const lf_budget* b,
+                                     int32_t* indices, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  if (!Q || !s || !b || !indices) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, b, &dm);
+  if (rc != LF_OK) return rc;
+  if (dm.F > max_frames) return LF_ERR_SHAPE;
+  const size_t need = kcache_bytes(dm, max_frames);
+  if (need == 0) return LF_ERR_SHAPE;
+  if (!kcache || kcache_bytes_given < need) return LF_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < (size_t)dm.H * dm.n_q * dm.d * sizeof(float))
+    return LF_ERR_WORKSPACE;
+  if (misaligned(Q, 16) || misaligned(Kcache, 16) || misaligned(indices, 4) ||
+      misaligned(kcache, 256) || misaligned(workspace, 256))
+    return LF_ERR_ALIGN;
+  return lf_launch_select_cached(Q, Kcache, kcache, max_frames, s, b, &dm, indices, workspace, stream);
 }
 
 extern "C" int lf_sparse_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
@@ -229,4 +286,4 @@ extern "C" const char* lf_strerror(int status) {
   }
 }
 
-extern "C" int lf_version(void) { return 100; }
+extern "C" int lf_version(void) { return 200; }

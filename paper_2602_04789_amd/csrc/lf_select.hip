@@ -29,7 +29,9 @@ struct PoolArgs {
   float* qt;
   float* kt;
   int64_t q_stride_tok, q_stride_head, k_stride_tok, k_stride_head;
-  int n, nb, n_q, n_k;
+  int n, nb, n_q;
+  int k_block0, n_kp;   // KV blocks pooled by this launch: [k_block0, k_block0 + n_kp)
+  int kt_rows;          // rows of the quad-major pooled-key matrix (KV blocks it has room for)
 };
 
 // Pooled keys are stored "channel-quad major": element (row c, channel t) of a [rows][d]
@@ -49,11 +51,11 @@ __global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
   constexpr int RG = kThreads / CH;  // token rows in flight per pass
   __shared__ double red[RG][D];
 
-  const int per_head = a.n_q + a.n_k;
+  const int per_head = a.n_q + a.n_kp;
   const int h = blockIdx.x / per_head;
   const int u = blockIdx.x % per_head;
   const bool is_q = u < a.n_q;
-  const int c = is_q ? u : u - a.n_q;
+  const int c = is_q ? u : a.k_block0 + u - a.n_q;
   const int tau = c / a.nb, j = c % a.nb;
   const int tok0 = tau * a.n + j * 64;
   const int cnt = min(64, a.n - j * 64);
@@ -94,19 +96,21 @@ __global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
     if (is_q)
       a.qt[((int64_t)h * a.n_q + c) * D + threadIdx.x] = mean;
     else
-      a.kt[(int64_t)h * a.n_k * D + quad_major(a.n_k, c, threadIdx.x)] = mean;
+      a.kt[(int64_t)h * a.kt_rows * D + quad_major(a.kt_rows, c, threadIdx.x)] = mean;
   }
 }
 
-// k_hat[h][a][:] for candidate frame tau = n_sink + a: binary64 sum of the frame's nb block
-// means in ascending block order, / nb, rounded to float32.  One thread per channel quad.
+// k_hat of frames tau0 .. tau0 + count - 1, written to rows out0 .. of the quad-major matrix
+// kh (kh_rows rows per head): binary64 sum of the frame's nb block means in ascending block
+// order, / nb, rounded to float32.  One thread per channel quad.
 __global__ void lf_frame_mean_kernel(const float* __restrict__ kt, float* __restrict__ kh,
-                                     int d, int nb, int n_k, int m, int n_sink) {
-  const int h = blockIdx.x / m, a = blockIdx.x % m;
-  const int tau = n_sink + a;
+                                     int d, int nb, int kt_rows, int kh_rows, int tau0, int out0,
+                                     int count) {
+  const int h = blockIdx.x / count, a = blockIdx.x % count;
+  const int tau = tau0 + a;
   for (int q = threadIdx.x; q < d / 4; q += blockDim.x) {
-    const float4* src = reinterpret_cast<const float4*>(kt + (int64_t)h * n_k * d) +
-                        ((int64_t)q * n_k + (int64_t)tau * nb);
+    const float4* src = reinterpret_cast<const float4*>(kt + (int64_t)h * kt_rows * d) +
+                        ((int64_t)q * kt_rows + (int64_t)tau * nb);
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     int j = 0;
     for (; j + 8 <= nb; j += 8) {
@@ -125,7 +129,7 @@ __global__ void lf_frame_mean_kernel(const float* __restrict__ kt, float* __rest
     float4 o;
     o.x = (float)(s0 / (double)nb); o.y = (float)(s1 / (double)nb);
     o.z = (float)(s2 / (double)nb); o.w = (float)(s3 / (double)nb);
-    reinterpret_cast<float4*>(kh + (int64_t)h * m * d)[(int64_t)q * m + a] = o;
+    reinterpret_cast<float4*>(kh + (int64_t)h * kh_rows * d)[(int64_t)q * kh_rows + out0 + a] = o;
   }
 }
 
@@ -137,6 +141,8 @@ struct SelectArgs {
   int d, nb, n_q, n_k, F_h, f, m;
   int n_sink, n_win, k_frames, k_blocks, current_mandatory, list_len;
   int n_cand, n_tf;
+  int kt_rows, kh_rows;  // rows per head of the quad-major matrices kt and kh
+  int kh_row0;           // row of kh that holds candidate frame 0 (frame n_sink)
 };
 
 // Dynamic LDS of lf_select_kernel<D, E>; must mirror the carving at the top of the kernel.
@@ -274,8 +280,8 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   // Eq. 8: frame-level scores against the candidate frames M = [n_sink, F_h - n_win).
   const bool retrieve = a.k_frames < a.m;
   if (retrieve) {
-    const float4* khh = reinterpret_cast<const float4*>(a.kh + (int64_t)h * a.m * D);
-    for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh + c, a.m);
+    const float4* khh = reinterpret_cast<const float4*>(a.kh + (int64_t)h * a.kh_rows * D) + a.kh_row0;
+    for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh + c, a.kh_rows);
   }
   __syncthreads();
 
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   float s[E];
   int p[E];
   {
-    const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.n_k * D);
+    const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.kt_rows * D);
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const int i = e * kThreads + tid;
@@ -310,7 +316,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
       p[e] = 0x7fffffff;
       if (i < a.n_cand) {
         const int c = flist[i / a.nb] * a.nb + i % a.nb;
-        s[e] = dot_quad_major<D>(qd, kth + c, a.n_k);
+        s[e] = dot_quad_major<D>(qd, kth + c, a.kt_rows);
         p[e] = i;
         sel[i] = 0;
       }
@@ -355,14 +361,10 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
 
 }  // namespace
 
-int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_budget* b,
-                     const lf_dims* dm, int32_t* indices, void* workspace, void* stream) {
-  hipStream_t st = (hipStream_t)stream;
-  char* ws = (char*)workspace;
-  float* qt = (float*)(ws + dm->off_qt);
-  float* kt = (float*)(ws + dm->off_kt);
-  float* kh = (float*)(ws + dm->off_kh);
-
+// Pools query blocks (when Q is given) and the KV blocks of frames [frame0, frame1) into qt / the
+// quad-major matrix kt with kt_rows rows per head.
+static void launch_pool(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
+                        float* kt, int kt_rows, int frame0, int frame1, hipStream_t st) {
   PoolArgs pa;
   pa.Q = (const uint16_t*)Q;
   pa.K = (const uint16_t*)K;
@@ -374,19 +376,21 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
   pa.k_stride_head = s->k_stride_head;
   pa.n = dm->n;
   pa.nb = dm->nb;
-  pa.n_q = dm->n_q;
-  pa.n_k = dm->n_k;
-  const unsigned pool_grid = (unsigned)(dm->H * (dm->n_q + dm->n_k));
+  pa.n_q = Q ? dm->n_q : 0;
+  pa.k_block0 = frame0 * dm->nb;
+  pa.n_kp = (frame1 - frame0) * dm->nb;
+  pa.kt_rows = kt_rows;
+  const unsigned pool_grid = (unsigned)(dm->H * (pa.n_q + pa.n_kp));
+  if (pool_grid == 0) return;
   if (dm->d == 128)
     hipLaunchKernelGGL(lf_pool_kernel<128>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
   else
     hipLaunchKernelGGL(lf_pool_kernel<64>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
+}
 
-  const bool retrieve = b->k_frames < dm->m;
-  if (retrieve)
-    hipLaunchKernelGGL(lf_frame_mean_kernel, dim3((unsigned)(dm->H * dm->m)), dim3(dm->d), 0, st,
-                       kt, kh, dm->d, dm->nb, dm->n_k, dm->m, b->n_sink);
-
+static void launch_select(const lf_budget* b, const lf_dims* dm, const float* qt, const float* kt,
+                          const float* kh, int kt_rows, int kh_rows, int kh_row0, int32_t* indices,
+                          hipStream_t st) {
   SelectArgs sa;
   sa.qt = qt;
   sa.kt = kt;
@@ -407,6 +411,9 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
   sa.list_len = b->list_len;
   sa.n_cand = dm->n_cand;
   sa.n_tf = dm->n_tf;
+  sa.kt_rows = kt_rows;
+  sa.kh_rows = kh_rows;
+  sa.kh_row0 = kh_row0;
   // E = candidate pairs per thread in the sort: 256*E >= n_cand, E a power of two
   int e = 1;
   while (kThreads * e < dm->n_cand) e <<= 1;
@@ -422,5 +429,51 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
     else if (e == 4) LF_LAUNCH_SELECT(64, 4); else LF_LAUNCH_SELECT(64, 8);
   }
 #undef LF_LAUNCH_SELECT
+}
+
+int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_budget* b,
+                     const lf_dims* dm, int32_t* indices, void* workspace, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* qt = (float*)(ws + dm->off_qt);
+  float* kt = (float*)(ws + dm->off_kt);
+  float* kh = (float*)(ws + dm->off_kh);
+  launch_pool(Q, K, s, dm, qt, kt, dm->n_k, 0, dm->F, st);
+  const bool retrieve = b->k_frames < dm->m;
+  if (retrieve)
+    hipLaunchKernelGGL(lf_frame_mean_kernel, dim3((unsigned)(dm->H * dm->m)), dim3(dm->d), 0, st,
+                       kt, kh, dm->d, dm->nb, dm->n_k, dm->m, b->n_sink, 0, dm->m);
+  launch_select(b, dm, qt, kt, kh, dm->n_k, dm->m > 0 ? dm->m : 1, 0, indices, st);
+  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+}
+
+// Pooled-key cache: kt for max_frames * nb blocks, then kh for max_frames frames (all frames,
+// row = absolute frame index), both quad-major per head.
+int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm, int frame0, int frame1,
+                            int max_frames, void* kcache, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  float* kt = (float*)kcache;
+  float* kh = kt + (size_t)dm->H * max_frames * dm->nb * dm->d;
+  launch_pool(nullptr, K, s, dm, nullptr, kt, max_frames * dm->nb, frame0, frame1, st);
+  hipLaunchKernelGGL(lf_frame_mean_kernel, dim3((unsigned)(dm->H * (frame1 - frame0))), dim3(dm->d), 0, st,
+                     kt, kh, dm->d, dm->nb, max_frames * dm->nb, max_frames, frame0, frame0,
+                     frame1 - frame0);
+  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+}
+
+int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
+                            const lf_shape* s, const lf_budget* b, const lf_dims* dm, int32_t* indices,
+                            void* workspace, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  float* qt = (float*)workspace;
+  float* kt = (float*)kcache;
+  const float* kh = kt + (size_t)dm->H * max_frames * dm->nb * dm->d;
+  // one launch pools Q and, when the keys are given, the block means of the current chunk
+  // (its frame means are not needed while it is current: the candidate frames are history)
+  if (Kcur)
+    launch_pool(Q, Kcur, s, dm, qt, kt, max_frames * dm->nb, dm->F_h, dm->F, st);
+  else
+    launch_pool(Q, nullptr, s, dm, qt, nullptr, 1, 0, 0, st);
+  launch_select(b, dm, qt, kt, kh, max_frames * dm->nb, max_frames, b->n_sink, indices, st);
   return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
 }

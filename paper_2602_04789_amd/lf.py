@@ -84,6 +84,14 @@ def load() -> C.CDLL:
     lib.lf_sparse_attn.argtypes = [vp, vp, vp, C.POINTER(lf_shape), vp, C.c_int32, C.c_float,
                                    vp, vp]
     lib.lf_sparse_attn.restype = C.c_int
+    lib.lf_kcache_bytes.argtypes = [C.POINTER(lf_shape), C.c_int32]
+    lib.lf_kcache_bytes.restype = C.c_size_t
+    lib.lf_kcache_update.argtypes = [vp, C.POINTER(lf_shape), C.c_int32, C.c_int32, C.c_int32, vp,
+                                     C.c_size_t, vp]
+    lib.lf_kcache_update.restype = C.c_int
+    lib.lf_select_mask_cached.argtypes = [vp, vp, vp, C.c_size_t, C.c_int32, C.POINTER(lf_shape),
+                                          C.POINTER(lf_budget), vp, vp, C.c_size_t, vp]
+    lib.lf_select_mask_cached.restype = C.c_int
     lib.lf_strerror.argtypes = [C.c_int]
     lib.lf_strerror.restype = C.c_char_p
     lib.lf_version.argtypes = []
@@ -182,6 +190,54 @@ def lf_select_mask(Q, Kcache, frame_len: int, block: int, budget: lf_budget, ind
                             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if rc != LF_OK:
         raise LfError(rc, "lf_select_mask")
+    return indices
+
+
+def lf_kcache_bytes(shape: lf_shape, max_frames: int) -> int:
+    return int(load().lf_kcache_bytes(C.byref(shape), int(max_frames)))
+
+
+def lf_kcache_update(Kcache, frame_len: int, block: int, frame_begin: int, frame_end: int,
+                     max_frames: int, kcache, stream=None):
+    """Pool frames [frame_begin, frame_end) of Kcache into the pooled-key cache ``kcache``
+    (a uint8 device tensor of >= lf_kcache_bytes())."""
+    _check_tensor(Kcache, "Kcache")
+    # the shape only has to describe K here: a query of one frame stands in for Q
+    sh = make_shape(Kcache[:, :frame_len], Kcache, frame_len=frame_len, block=block)
+    rc = load().lf_kcache_update(Kcache.data_ptr(), C.byref(sh), int(frame_begin), int(frame_end),
+                                 int(max_frames), kcache.data_ptr(),
+                                 kcache.numel() * kcache.element_size(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_kcache_update")
+
+
+def lf_select_mask_cached(Q, kcache, max_frames: int, kv_len: int, frame_len: int, block: int,
+                          budget: lf_budget, Kcache=None, indices=None, workspace=None, stream=None):
+    """Mask selection with the pooled keys taken from ``kcache``; returns the index tensor.
+    With ``Kcache`` the current chunk's block means are refreshed from it in the same call."""
+    import torch
+    _check_tensor(Q, "Q")
+    if Kcache is not None:
+        _check_tensor(Kcache, "Kcache")
+    sh = make_shape(Q, Q if Kcache is None else Kcache, frame_len=frame_len, block=block)
+    sh.kv_len = int(kv_len)
+    nb = -(-frame_len // block)
+    n_q = (sh.q_len // frame_len) * nb if frame_len > 0 else 0
+    if indices is None:
+        indices = torch.empty((sh.heads, n_q, max(int(budget.list_len), 0)), dtype=torch.int32,
+                              device=Q.device)
+    if workspace is None:
+        workspace = torch.empty(max(sh.heads * n_q * sh.head_dim * 4, 256), dtype=torch.uint8,
+                                device=Q.device)
+    rc = load().lf_select_mask_cached(Q.data_ptr(), None if Kcache is None else Kcache.data_ptr(),
+                                      kcache.data_ptr(),
+                                      kcache.numel() * kcache.element_size(), int(max_frames),
+                                      C.byref(sh), C.byref(budget), indices.data_ptr(),
+                                      workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(),
+                                      _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_select_mask_cached")
     return indices
 
 

@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(lf_[a-z_]+)\s*\(", text))
     assert {"lf_chunk_budget", "lf_select_mask", "lf_sparse_attn", "lf_workspace_bytes",
-            "lf_workspace_layout", "lf_strerror", "lf_version"} <= names
+            "lf_workspace_layout", "lf_strerror", "lf_version", "lf_kcache_bytes",
+            "lf_kcache_update", "lf_select_mask_cached"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert lf.lf_version() >= 100
@@ -134,6 +135,36 @@ def test_select_mask_argument_errors_enqueue_nothing(lib):
         _, _, b2 = _good()
         setattr(b2, field, bad)
         assert call(bb=b2) == -3, field
+
+
+def test_kcache_size_and_argument_errors_enqueue_nothing(lib):
+    w, sh, b = _good()           # last chunk: 21 frames of 25 blocks, 12 heads x 128
+    need = lf.lf_kcache_bytes(sh, 21)
+    assert need == 12 * (21 * 25 + 21) * 128 * 4
+    assert lf.lf_kcache_bytes(sh, 24) > need
+    assert lf.lf_kcache_bytes(sh, 0) == 0 and lf.lf_kcache_bytes(sh, 1 << 20) == 0
+    _, bad, _ = _good()
+    bad.head_dim = 96
+    assert lf.lf_kcache_bytes(bad, 21) == 0
+    upd = lambda K=FAKE, s=sh, f0=0, f1=21, mf=21, kc=FAKE, nbytes=need: lib.lf_kcache_update(
+        K, C.byref(s) if s is not None else None, f0, f1, mf, kc, nbytes, None)
+    assert upd(K=None) == -1 and upd(s=None) == -1
+    assert upd(f0=-1) == -2 and upd(f0=5, f1=4) == -2 and upd(f1=22) == -2 and upd(mf=20) == -2
+    assert upd(kc=None) == -6 and upd(nbytes=need - 1) == -6
+    assert upd(K=FAKE + 4) == -5 and upd(kc=FAKE + 64) == -5
+    assert upd(f0=7, f1=7) == 0          # empty range: nothing to do, nothing enqueued
+    qbytes = 12 * 75 * 128 * 4
+    sel = lambda Q=FAKE, K=None, kc=FAKE, nbytes=need, mf=21, s=sh, bb=b, idx=FAKE, ws=FAKE, wsb=qbytes: \
+        lib.lf_select_mask_cached(Q, K, kc, nbytes, mf, C.byref(s) if s is not None else None,
+                                  C.byref(bb) if bb is not None else None, idx, ws, wsb, None)
+    assert sel(Q=None) == -1 and sel(idx=None) == -1 and sel(s=None) == -1 and sel(bb=None) == -1
+    assert sel(kc=None) == -6 and sel(nbytes=need - 1) == -6
+    assert sel(ws=None) == -6 and sel(wsb=qbytes - 1) == -6
+    assert sel(mf=20) == -2
+    assert sel(Q=FAKE + 2) == -5 and sel(kc=FAKE + 16) == -5 and sel(K=FAKE + 8) == -5
+    _, _, b2 = _good()
+    b2.k_blocks += 1
+    assert sel(bb=b2) == -3
 
 
 def test_sparse_attn_argument_errors_enqueue_nothing(lib):

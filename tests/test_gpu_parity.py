@@ -215,6 +215,46 @@ def test_attention_list_edge_cases(gpu):
     assert float(Obuf[:, 0].abs().max()) == 0 and float(Obuf[:, :, w.head_dim:].abs().max()) == 0
 
 
+def test_pooled_key_cache_gives_the_same_lists(gpu):
+    """A rollout with the pooled-key cache: history frames are pooled once, when their chunk is
+    current; every call pools only Q and the current chunk.  Lists must equal those of the
+    stateless call (and so the oracle's) bit for bit, also after the current chunk's keys change
+    between two steps of the same chunk."""
+    torch, lf = gpu
+    last = synth.small_ragged(chunk_idx=5, heads=3)
+    xk = synth.make_inputs(last)
+    n, f, max_frames = last.frame_len, last.frames_per_chunk, last.frames + 2
+    Kall = _dev(torch, xk["K"])
+    sh_full = lf.make_shape(Kall[:, :f * n], Kall, frame_len=n, block=last.block)
+    kc = torch.zeros(lf.lf_kcache_bytes(sh_full, max_frames), dtype=torch.uint8, device="cuda")
+    for chunk in range(1, 6):
+        w = synth.small_ragged(chunk_idx=chunk, heads=3)
+        x = synth.make_inputs(w)
+        Q = _dev(torch, x["Q"])
+        K = Kall[:, :w.frames * n].clone()
+        b = lf.lf_chunk_budget(chunk, w.schedule)
+        for step in range(2):
+            if step == 1:   # the chunk being denoised changes between steps
+                K[:, w.hist_frames * n:] = _dev(torch, x["K"])[:, w.hist_frames * n:]
+            if step == 0:   # two ways to bring the current chunk in: a separate update ...
+                lf.lf_kcache_update(K, n, w.block, w.hist_frames, w.frames, max_frames, kc)
+                got = lf.lf_select_mask_cached(Q, kc, max_frames, w.frames * n, n, w.block, b)
+            else:           # ... or together with the selection
+                got = lf.lf_select_mask_cached(Q, kc, max_frames, w.frames * n, n, w.block, b, Kcache=K)
+            want = lf.lf_select_mask(Q, K, n, w.block, b)
+            torch.cuda.synchronize()
+            assert torch.equal(got, want), (chunk, step)
+        if chunk == 4:
+            Kf = K.view(torch.int16).cpu().numpy().view(np.uint16)
+            ob = O.chunk_budget(chunk, w.schedule)
+            ref = O.select_mask(_host_f32(x["Q"]), _host_f32(Kf), n, w.block, ob)
+            assert np.array_equal(got.cpu().numpy(), ref)
+        # commit the chunk: its final keys are the ones of the shared history
+        lf.lf_kcache_update(Kall[:, :w.frames * n], n, w.block, w.hist_frames, w.frames, max_frames, kc)
+    with pytest.raises(lf.LfError):
+        lf.lf_kcache_update(Kall, n, last.block, 0, last.frames + 1, max_frames, kc)
+
+
 def test_calls_are_deterministic(gpu):
     torch, lf = gpu
     w = synth.small_ragged(chunk_idx=4)
