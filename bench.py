@@ -49,7 +49,9 @@ def _workloads():
             "last_chunk": synth.cfg_last_chunk, "tiny": synth.cfg_tiny,
             # the paper's own operating point (1536 tokens per frame, Chunk-Aware Growth,
             # current chunk competing) at its fourth and its last chunk
-            "paper5s_mid": lambda: synth.cfg_paper_5s(4), "paper5s_last": lambda: synth.cfg_paper_5s(7)}
+            "paper5s_mid": lambda: synth.cfg_paper_5s(4), "paper5s_last": lambda: synth.cfg_paper_5s(7),
+            # the 15-second setting: 21 chunks, at chunk 20 the cache holds 57 history frames
+            "paper15s_late": lambda: synth.cfg_paper_15s(20)}
 
 
 def kept_flops(lists: np.ndarray, w) -> float:

@@ -259,6 +259,17 @@ def cfg_paper_5s(chunk_idx: int, heads: int = 12) -> Workload:
                     decay=True, sink=True, q_follow=True)
 
 
+def cfg_paper_15s(chunk_idx: int, heads: int = 12) -> Workload:
+    """The paper's 15-second setting (hyper-parameter table): 21 chunks, s_target 0.85 /
+    s_base 0.95, 3 retained past frames of which 1 sink + 1 window, otherwise as the
+    5-second operating point."""
+    s = _sched(mode=SCHED_CAG, n_chunks=21, frame_len=1536, n_sink=1, n_win=1, k_frames=1,
+               ratio_of=OF_ALL, current_mandatory=0, first_chunk_dense=1,
+               s_base=0.95, s_target=0.85)
+    return Workload(f"paper15s_c{chunk_idx}", heads, 128, 1536, 3, chunk_idx, s, seed=6,
+                    decay=True, sink=True, q_follow=True)
+
+
 def scaled(w: Workload, **kw) -> Workload:
     """A copy of ``w`` with fields replaced (schedule fields via ``schedule=``)."""
     return replace(w, **kw)

@@ -48,6 +48,7 @@ def _all_schedules():
     yield synth.cfg_last_chunk().schedule, range(1, 8)
     yield synth.cfg_rollout(1, 0).schedule, range(1, 8)
     yield synth.cfg_paper_5s(1).schedule, range(1, 8)
+    yield synth.cfg_paper_15s(1).schedule, range(1, 22)
     for mode in (0, 1, 2):
         for ratio_of in (0, 1, 2):
             for cm in (0, 1):

@@ -296,6 +296,7 @@ FULL = {
     # the paper's own operating point (Experimental Details; hyper-parameter table)
     "paper5s_mid": lambda: synth.cfg_paper_5s(4),
     "paper5s_last": lambda: synth.cfg_paper_5s(7),
+    "paper15s_late": lambda: synth.cfg_paper_15s(20),   # 57 history frames, 54 of them candidates
 }
 
 
