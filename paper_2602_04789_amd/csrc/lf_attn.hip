@@ -112,6 +112,10 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         qf[s].u = *reinterpret_cast<const uint4*>(qp + s * 16 + kg * 8);
       else
         qf[s].u = make_uint4(0, 0, 0, 0);
+      // scores are wanted in the exp2 domain: fold softmax_scale * log2(e) into Q once
+      // (one bfloat16 rounding of Q instead of one multiply per score)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[s].v[e] = (__bf16)((float)qf[s].v[e] * a.c);
     }
   }
 
@@ -184,28 +188,35 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // V^T (A operand of O^T) through the transposing LDS read: within each group of 16 lanes,
   // lane 4e+g supplies the address of row e, columns 4g..4g+3, and lane i receives column i
   // of the four rows.  vaddr[u][half][mb] is in units of bf16 elements.
-  int vaddr[2][2][MB];
+  int vbase[MB];
   {
     const int i16 = lane & 15;
     const int tr_row = 32 * kh + 4 * kg + (i16 >> 2);
     const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const int row = tr_row + 16 * u + 8 * hf, col = 32 * mb + tr_col;
-          vaddr[u][hf][mb] = (row * CH + v_swz<CH>(row, col >> 3)) * 8 + (col & 7);
-        }
+    for (int mb = 0; mb < MB; ++mb) {
+      const int col = 32 * mb + tr_col;
+      vbase[mb] = (tr_row * CH + v_swz<CH>(tr_row, col >> 3)) * 8 + (col & 7);
+    }
   }
+  // k-step u, half hf: 16 u + 8 hf rows further, which the swizzle does not notice
+  auto vaddr = [&](int u, int hf, int mb) { return vbase[mb] + (16 * u + 8 * hf) * CH * 8; };
 
   f32x16 oacc[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
-  float m_run = -1.0e30f, l_run = 0.0f;
+  // Online softmax with a lazily updated reference: S^T accumulators start at -m_run, so the
+  // matrix core delivers s - m_run and P = exp2 of that needs no further arithmetic.  m_run
+  // moves only when a row's score exceeds it by more than kTau (P <= 2^kTau otherwise, well
+  // inside bfloat16 and float32 range), or when the row sees its first unmasked score.
+  constexpr float kTau = 8.0f;
+  float m_run = 0.0f, l_run = 0.0f;
+  bool seen = false;
+  f32x16 seed;   // -m_run in all 16 accumulators
+#pragma unroll
+  for (int i = 0; i < 16; ++i) seed[i] = 0.0f;
   constexpr int H1 = (LPW + 1) / 2;  // loads issued in the first of the two slots of a phase
 
   // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
@@ -239,13 +250,10 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[s0 + s].v, acc, 0, 0, 0);
       return acc;
     };
-    f32x16 zero16;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     lds_barrier();
-    f32x16 sacc = s_half(buf0, s_half(buf0, zero16, 0), KS / 2);
+    f32x16 sacc = s_half(buf0, s_half(buf0, seed, 0), KS / 2);
 
     // Past the end of the list the pipeline runs on the last entry again: its loads and its
     // S^T are redundant and unused, which keeps the loop body free of branches.
@@ -263,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           if (kv >= cnt) sacc[i] = -INFINITY;
         }
       }
-      f32x16 snext = s_half(other, zero16, 0);
+      f32x16 snext = s_half(other, seed, 0);
       float mx = fmaxf(fmaxf(sacc[0], sacc[1]), fmaxf(sacc[2], sacc[3]));
 #pragma unroll
       for (int i = 4; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sacc[i], sacc[i + 1]));
@@ -272,23 +280,32 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
       }
-      const float m_new = fmaxf(m_run, mx * a.c);
+      const bool grow = mx > kTau || (!seen && mx > -INFINITY);
       fetch_k(krs, cur, H1, LPW);
-      if (__ballot(m_new > m_run) != 0ull) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      snext = s_half(other, snext, KS / 2);
+      if (__ballot(grow) != 0ull) {
+        // move the reference by delta: everything held relative to it follows
+        const float delta = grow ? mx : 0.0f;
+        const float alpha = __builtin_amdgcn_exp2f(-delta);
+        m_run += delta;
+        seen = seen || grow;
         l_run *= alpha;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
-        m_run = m_new;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          sacc[i] -= delta;
+          snext[i] -= delta;
+          seed[i] -= delta;
+        }
       }
       fetch_v(vrs, other, 0, H1);
-      snext = s_half(other, snext, KS / 2);
 
       float p[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -m_run));
+      for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(sacc[i]);
 
       // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
       // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
@@ -307,8 +324,8 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr[u][0][mb]));
-          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr[u][1][mb]));
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 0, mb)));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 1, mb)));
           const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
         }
@@ -328,6 +345,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // Merge the two KV halves, one query-row half at a time through one LDS buffer:
   // wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine and store.
   l_run += __shfl_xor(l_run, 32);
+  if (!seen) m_run = -1.0e30f;  // a row that never saw an unmasked score carries no weight
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   float* mbuf = reinterpret_cast<float*>(buf0);  // [MB*16][64]
   for (int phase = 0; phase < 2; ++phase) {
