@@ -112,10 +112,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         qf[s].u = *reinterpret_cast<const uint4*>(qp + s * 16 + kg * 8);
       else
         qf[s].u = make_uint4(0, 0, 0, 0);
-      // scores are wanted in the exp2 domain: fold softmax_scale * log2(e) into Q once
-      // (one bfloat16 rounding of Q instead of one multiply per score)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[s].v[e] = (__bf16)((float)qf[s].v[e] * a.c);
     }
   }
 
@@ -207,16 +203,14 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[mb][i] = 0.0f;
-  // Online softmax with a lazily updated reference: S^T accumulators start at -m_run, so the
-  // matrix core delivers s - m_run and P = exp2 of that needs no further arithmetic.  m_run
-  // moves only when a row's score exceeds it by more than kTau (P <= 2^kTau otherwise, well
-  // inside bfloat16 and float32 range), or when the row sees its first unmasked score.
-  constexpr float kTau = 8.0f;
-  float m_run = 0.0f, l_run = 0.0f;
-  bool seen = false;
-  f32x16 seed;   // -m_run in all 16 accumulators
-#pragma unroll
-  for (int i = 0; i < 16; ++i) seed[i] = 0.0f;
+  // Online softmax in the exp2 domain with a lazily updated reference m_run: P = exp2(s c -
+  // m_run) is formed without looking for the row maximum first, and m_run is checked through
+  // the row sum afterwards.  It moves when the sum leaves the range below (a score far above
+  // the reference; +inf if exp2 overflowed, which is also how a row's first score announces
+  // itself, m_run starting at -1e30).  bfloat16 and float32 share their exponent range, so P,
+  // the row sums and O stay finite far beyond that range, and O / l does not depend on m_run.
+  constexpr float kSumMax = 1.0e30f;
+  float m_run = -1.0e30f, l_run = 0.0f;
   constexpr int H1 = (LPW + 1) / 2;  // loads issued in the first of the two slots of a phase
 
   // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
@@ -253,7 +247,10 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     lds_barrier();
-    f32x16 sacc = s_half(buf0, s_half(buf0, seed, 0), KS / 2);
+    f32x16 zero16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
+    f32x16 sacc = s_half(buf0, s_half(buf0, zero16, 0), KS / 2);
 
     // Past the end of the list the pipeline runs on the last entry again: its loads and its
     // S^T are redundant and unused, which keeps the loop body free of branches.
@@ -271,63 +268,61 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           if (kv >= cnt) sacc[i] = -INFINITY;
         }
       }
-      f32x16 snext = s_half(other, seed, 0);
-      float mx = fmaxf(fmaxf(sacc[0], sacc[1]), fmaxf(sacc[2], sacc[3]));
+      f32x16 snext = s_half(other, zero16, 0);
+      // P^T = exp2(s c - m_run), packed to bfloat16 in the
+      // B-operand layout of the second product; row sums from the packed values.
+      bf16x8 pf[2];
+      float l_new = l_run;
+      auto softmax = [&]() __attribute__((always_inline)) {
+        l_new = l_run;
 #pragma unroll
-      for (int i = 4; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sacc[i], sacc[i + 1]));
-      {
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf[u][e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[8 * u + e], a.c, -m_run));
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const bf16x2 pr = {pf[u][e], pf[u][e + 1]};
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+            l_new = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_new, false);
+          }
+        }
+      };
+      softmax();
+      fetch_k(krs, cur, H1, LPW);
+      snext = s_half(other, snext, KS / 2);
+      // Rare: the row sum says the reference is far too low (or was never set).  Then the
+      // maxima are taken, the reference moves up to them and P^T is made again.
+      if (__ballot(l_new > kSumMax) != 0ull) {
+        float mx = fmaxf(fmaxf(sacc[0], sacc[1]), fmaxf(sacc[2], sacc[3]));
+#pragma unroll
+        for (int i = 4; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sacc[i], sacc[i + 1]));
         // lanes l and l+32 hold the same query column: exchange through the lane-swap unit
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-      }
-      const bool grow = mx > kTau || (!seen && mx > -INFINITY);
-      fetch_k(krs, cur, H1, LPW);
-      snext = s_half(other, snext, KS / 2);
-      if (__ballot(grow) != 0ull) {
-        // move the reference by delta: everything held relative to it follows
-        const float delta = grow ? mx : 0.0f;
-        const float alpha = __builtin_amdgcn_exp2f(-delta);
-        m_run += delta;
-        seen = seen || grow;
+        const float m_new = fmaxf(m_run, mx * a.c);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
         l_run *= alpha;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) oacc[mb][i] *= alpha;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          sacc[i] -= delta;
-          snext[i] -= delta;
-          seed[i] -= delta;
-        }
+        softmax();
       }
+      l_run = l_new;
       fetch_v(vrs, other, 0, H1);
-
-      float p[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(sacc[i]);
 
       // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
       // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
       const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(cur + TILE);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[8 * u + e];
-        // row sums of P as rounded for the product, two values per instruction
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const bf16x2 pr = {pf[e], pf[e + 1]};
-          const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
-        }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
           const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 0, mb)));
           const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 1, mb)));
           const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[mb], 0, 0, 0);
+          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[mb], 0, 0, 0);
         }
       }
       fetch_v(vrs, other, H1, LPW);
@@ -345,7 +340,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // Merge the two KV halves, one query-row half at a time through one LDS buffer:
   // wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine and store.
   l_run += __shfl_xor(l_run, 32);
-  if (!seen) m_run = -1.0e30f;  // a row that never saw an unmasked score carries no weight
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   float* mbuf = reinterpret_cast<float*>(buf0);  // [MB*16][64]
   for (int phase = 0; phase < 2; ++phase) {

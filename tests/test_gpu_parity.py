@@ -215,6 +215,43 @@ def test_attention_list_edge_cases(gpu):
     assert float(Obuf[:, 0].abs().max()) == 0 and float(Obuf[:, :, w.head_dim:].abs().max()) == 0
 
 
+@pytest.mark.parametrize("scale", [0.25, 1.0, 4.0])
+def test_attention_with_extreme_logits(gpu, scale):
+    """Logits far outside the usual range (softmax_scale 0.25, 1 and 4 instead of 1/sqrt(d) =
+    0.088: tens to hundreds in the exp2 domain, rising and falling from tile to tile, beyond what
+    exp2 holds in float32): the reference of the online softmax has to move, nothing may
+    overflow, and the usual tolerance still holds (the scale is applied to the float32 scores,
+    not folded into a bfloat16 operand)."""
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=4, heads=2)
+    x = synth.make_inputs(w)
+    n = w.frame_len
+    K = x["K"].copy()
+    Kf = _host_f32(K)
+    Kf[:, 0:n] *= 0.05          # a first frame with tiny logits, then much larger ones
+    Kf[:, 2 * n:3 * n] *= 3.0
+    K = synth.f32_to_bf16_bits(Kf)
+    Q, Kd, V = _dev(torch, x["Q"]), _dev(torch, K), _dev(torch, x["V"])
+    lists = O.full_lists(w.heads, w.frame_len, w.block, w.frames_per_chunk, w.frames)
+    idx = torch.from_numpy(lists).cuda()
+    out = lf.lf_sparse_attn(Q, Kd, V, idx, w.frame_len, w.block, softmax_scale=scale)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    Qf, Kf, Vf = _host_f32(x["Q"]), _host_f32(K), _host_f32(x["V"])
+    n_q = lists.shape[1]
+    worst = 0.0
+    for h in range(w.heads):
+        for r in range(0, n_q, 3):
+            lo, hi = O.block_token_range(r, w.frame_len, w.block)
+            ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, list(lists[h, r]), w.frame_len,
+                                           w.block, scale=scale)
+            err = np.abs(got[h, lo:hi] - ref)
+            worst = max(worst, float(err.max()))
+            assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (h, r, err.max(), err.mean())
+    print(f"extreme logits, scale {scale}: max-abs {worst:.2e}", flush=True)
+
+
 def test_pooled_key_cache_gives_the_same_lists(gpu):
     """A rollout with the pooled-key cache: history frames are pooled once, when their chunk is
     current; every call pools only Q and the current chunk.  Lists must equal those of the
