@@ -150,6 +150,7 @@ def run_rollout(args, torch, lf, synth):
     for chunk in range(1, 8):
         for step_i in range(4):
             w = synth.cfg_rollout(chunk, step_i)
+            print(f"rollout: generating chunk {chunk} step {step_i}", file=sys.stderr, flush=True)
             x = synth.make_inputs(w)
             Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
             sched = lf.make_schedule(w.schedule)
