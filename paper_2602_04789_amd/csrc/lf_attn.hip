@@ -102,6 +102,17 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   const int q_cnt = min(64, a.n - (r % a.nb) * 64);
   const int qrow = 32 * rh + ln;
 
+  // The list entries of the first pass are requested first, so that they travel together with
+  // the Q fragments instead of after them.
+  const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
+  constexpr int EPT = kMaxEnt / kThreads;   // list entries per thread and pass
+  int pre[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int i = tid + j * kThreads;
+    pre[j] = i < a.list_len ? list[i] : -1;
+  }
+
   // Q^T fragments (B operand): lane (column q = ln, k-group kg) holds 8 consecutive channels.
   Frag qf[KS];
   {
@@ -115,7 +126,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     }
   }
 
-  const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
   const char* Kh = reinterpret_cast<const char*>(a.K + (int64_t)h * a.k_stride_head);
   const char* Vh = reinterpret_cast<const char*>(a.V + (int64_t)h * a.v_stride_head);
   const int64_t k_row_bytes = a.k_stride_tok * 2, v_row_bytes = a.v_stride_tok * 2;
@@ -219,11 +229,15 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     const int t1 = min(a.list_len, t0 + kMaxEnt);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    for (int i = t0 + tid; i < t1; i += kThreads) {
-      const int c = list[i];
-      const bool ok = (unsigned)c < (unsigned)a.n_k;
-      const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
-      ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int i = t0 + tid + e * kThreads;
+      if (i < t1) {
+        const int c = t0 == 0 ? pre[e] : list[i];
+        const bool ok = (unsigned)c < (unsigned)a.n_k;
+        const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+        ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+      }
     }
     __syncthreads();
     // Software pipeline, one tile deep: iteration t computes S^T of tile t+1 (matrix core)
@@ -337,42 +351,40 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     }
   }
 
-  // Merge the two KV halves, one query-row half at a time through one LDS buffer:
-  // wavefronts with kh = 1 publish (m, l, O^T), kh = 0 combine and store.
+  // Merge the two KV halves through LDS (the 32 KiB of the even-tile buffer hold both query
+  // halves): wavefronts with kh = 1 publish (m, l, O^T), those with kh = 0 combine and store.
   l_run += __shfl_xor(l_run, 32);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  float* mbuf = reinterpret_cast<float*>(buf0);  // [MB*16][64]
-  for (int phase = 0; phase < 2; ++phase) {
-    __syncthreads();
-    if (kh == 1 && rh == phase) {
-      ml[rh][0][lane] = m_run;
-      ml[rh][1][lane] = l_run;
+  float* mbuf = reinterpret_cast<float*>(buf0) + rh * (MB * 16 * 64);  // [MB*16][64] per query half
+  __syncthreads();
+  if (kh == 1) {
+    ml[rh][0][lane] = m_run;
+    ml[rh][1][lane] = l_run;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mbuf[(mb * 16 + i) * 64 + lane] = oacc[mb][i];
-    }
-    __syncthreads();
-    if (kh == 0 && rh == phase) {
-      const float m2 = ml[rh][0][lane], l2 = ml[rh][1][lane];
-      const float m = fmaxf(m_run, m2);
-      const float a1 = __builtin_amdgcn_exp2f(m_run - m), a2 = __builtin_amdgcn_exp2f(m2 - m);
-      const float inv = 1.0f / (l_run * a1 + l2 * a2);
-      if (qrow < q_cnt) {
-        uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
+      for (int i = 0; i < 16; ++i) mbuf[(mb * 16 + i) * 64 + lane] = oacc[mb][i];
+  }
+  __syncthreads();
+  if (kh == 0) {
+    const float m2 = ml[rh][0][lane], l2 = ml[rh][1][lane];
+    const float m = fmaxf(m_run, m2);
+    const float a1 = __builtin_amdgcn_exp2f(m_run - m), a2 = __builtin_amdgcn_exp2f(m2 - m);
+    const float inv = 1.0f / (l_run * a1 + l2 * a2);
+    if (qrow < q_cnt) {
+      uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
+      for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            bf16x4 o4;
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int i = 4 * g + e;
-              const float o2 = mbuf[(mb * 16 + i) * 64 + lane];
-              o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
-            }
-            *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * g + e;
+            const float o2 = mbuf[(mb * 16 + i) * 64 + lane];
+            o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
           }
+          *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
         }
       }
     }
