@@ -38,7 +38,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # the same run shows, WRITE_SIZE by 1.000): profiles/last_chunk_pmc_counters.txt.
 # None for workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("last_chunk", "attn"): (254600 * 1.994 + 14040) * 1024,
+    ("last_chunk", "attn"): (236500 * 1.994 + 14040) * 1024,
     ("last_chunk", "select"): ((56190 + 1454 + 8668) * 1.994 + (6752 + 180 + 675)) * 1024,
 }
 
@@ -214,6 +214,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
                     help="skip the library GEMM / streaming read measurements")
+    ap.add_argument("--no-cached-select", action="store_true",
+                    help="skip the pooled-key-cache variant of the selection (keeps profiles to the "
+                         "four kernels of the main path)")
     ap.add_argument("--cold", action="store_true",
                     help="also time one step right after streaming a 1 GiB buffer through the caches")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -322,32 +325,33 @@ def main():
                    "frac": sel_gbps / PEAK_HBM_GBPS, "bytes": sel_bytes,
                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "select"))},
     }
-    # Selection with the pooled-key cache: the history frames were pooled when their chunk was
-    # generated (not timed: it happened in earlier calls of the rollout); a call pools only Q
-    # and the chunk being denoised.
-    max_frames = w.frames
-    kc = torch.empty(lf.lf_kcache_bytes(sh, max_frames), dtype=torch.uint8, device="cuda")
-    lf.lf_kcache_update(K, w.frame_len, w.block, 0, w.hist_frames, max_frames, kc)
-    idx_c = torch.empty_like(idx)
+    if not args.no_cached_select:
+        # Selection with the pooled-key cache: the history frames were pooled when their chunk was
+        # generated (not timed: it happened in earlier calls of the rollout); a call pools only Q
+        # and the chunk being denoised.
+        max_frames = w.frames
+        kc = torch.empty(lf.lf_kcache_bytes(sh, max_frames), dtype=torch.uint8, device="cuda")
+        lf.lf_kcache_update(K, w.frame_len, w.block, 0, w.hist_frames, max_frames, kc)
+        idx_c = torch.empty_like(idx)
 
-    def cached():
-        lf.lf_select_mask_cached(Q, kc, max_frames, w.kv_len, w.frame_len, w.block, b, Kcache=K,
-                                 indices=idx_c, workspace=ws)
+        def cached():
+            lf.lf_select_mask_cached(Q, kc, max_frames, w.kv_len, w.frame_len, w.block, b, Kcache=K,
+                                     indices=idx_c, workspace=ws)
 
-    for _ in range(5):
-        cached()
-    ce = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(50)]
-    torch.cuda.synchronize()
-    for e in ce:
-        e[0].record()
-        cached()
-        e[1].record()
-    torch.cuda.synchronize()
-    c_ms = np.array([e[0].elapsed_time(e[1]) for e in ce])
-    c_bytes = float((w.q_len + w.q_len) * w.heads * w.head_dim * 2)   # Q and the current chunk's K
-    res["select_cached"] = {"ms": float(c_ms.mean()), "ms_median_min": [float(np.median(c_ms)), float(c_ms.min())],
-                            "bytes": c_bytes, "achieved": c_bytes / (c_ms.mean() * 1e-3) / 1e9,
-                            "unit": "GB/s", "lists_equal_uncached": bool(torch.equal(idx_c, idx))}
+        for _ in range(5):
+            cached()
+        ce = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(50)]
+        torch.cuda.synchronize()
+        for e in ce:
+            e[0].record()
+            cached()
+            e[1].record()
+        torch.cuda.synchronize()
+        c_ms = np.array([e[0].elapsed_time(e[1]) for e in ce])
+        c_bytes = float((w.q_len + w.q_len) * w.heads * w.head_dim * 2)   # Q and the current chunk's K
+        res["select_cached"] = {"ms": float(c_ms.mean()), "ms_median_min": [float(np.median(c_ms)), float(c_ms.min())],
+                                "bytes": c_bytes, "achieved": c_bytes / (c_ms.mean() * 1e-3) / 1e9,
+                                "unit": "GB/s", "lists_equal_uncached": bool(torch.equal(idx_c, idx))}
     if cold is not None:
         res["cold_after_1gib_stream"] = cold
     if not args.no_measured_peaks:

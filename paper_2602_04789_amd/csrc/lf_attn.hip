@@ -13,7 +13,10 @@
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with
 // v_mfma_f32_32x32x16_bf16: in the 32x32 accumulator layout a lane then holds one query
 // column and 16 KV rows, which is exactly the B-operand layout the second product wants,
-// so P never moves between lanes.  Softmax is float32, in the exp2 domain.
+// so P never moves between lanes.  Softmax is float32, in the exp2 domain, against a lazy
+// reference: P = exp2(s*c - m) with a per-row m that is moved (and O, l rescaled) only when a
+// row sum shows that it has fallen too far behind the scores; the common path takes no row
+// maximum.  The result is the same softmax: the reference cancels in O / l.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
