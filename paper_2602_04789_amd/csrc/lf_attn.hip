@@ -4,8 +4,9 @@
 // One workgroup (4 wavefronts) per (head, query block of 64 rows); two workgroups share a
 // compute unit, so every SIMD holds two wavefronts in different phases and the matrix core
 // of one overlaps the vector ALU of the other.  For each listed KV block the 64 x d K and V
-// tiles are brought into a double-buffered LDS tile by asynchronous global->LDS loads that
-// are issued a few at a time between the compute phases of the previous tile.  Wavefront
+// tiles are brought into a double-buffered LDS tile by asynchronous global->LDS loads, a
+// wavefront's share of a tile in one group (V of the next tile right after the barrier, K of
+// the tile after that in the middle of the step).  Wavefront
 // (rh, kh) owns query rows [32 rh, 32 rh + 32) and KV rows [32 kh, 32 kh + 32) of every tile
 // and keeps its own online-softmax state (m, l, O), so nothing crosses wavefronts inside
 // the loop; the two KV halves are merged once at the end.
@@ -142,8 +143,11 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     const int row = RPI * (LPW * wave + i) + ld_r;
-    koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + (uint32_t)k_swz<CH>(row, ld_p) * 16u;
-    voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + (uint32_t)v_swz<CH>(row, ld_p) * 16u;
+    // load i carries the immediate offset 1024 i, which moves its LDS target to the i-th stripe
+    // and is taken off the memory offset here (row >= RPI i and a row is at least 1024 / RPI
+    // bytes, so the difference is not negative)
+    koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + (uint32_t)k_swz<CH>(row, ld_p) * 16u - 1024u * i;
+    voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + (uint32_t)v_swz<CH>(row, ld_p) * 16u - 1024u * i;
   }
   // (first token, token count) of list entry t, wavefront-uniform.
   auto entry = [&](int t) -> int2 {
@@ -153,9 +157,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // The loads are raw buffer loads whose resource is the tile itself: base = the block's
   // first token, num_records = its token count x the row pitch.  Rows past a short block's
   // count are then out of range, which touches no memory and writes zeros, so the loads need
-  // no per-lane address arithmetic and no branch.  They are issued from inline assembly, a
-  // few at a time between the compute phases, so that the vector-memory queue never backs up
-  // into the issuing wavefront.
+  // no per-lane address arithmetic and no branch.  They are issued from inline assembly.
   auto tile_rsrc = [](const char* base, uint32_t row_bytes, int2 e) {
     int32x4 r;
     const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)e.x * row_bytes;
@@ -165,26 +167,28 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     r[3] = 0x00020000;
     return r;
   };
-  auto dma16 = [](int32x4 rs, uint32_t lds_addr, int lds_add, uint32_t voff) __attribute__((always_inline)) {
-    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rs), "i"(lds_add) : "scc");
-  };
-  // Loads i0 .. i1-1 (of LPW) of this wavefront's share of one tile.
-  auto fetch_part = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW], int i0, int i1)
-      __attribute__((always_inline)) {
+  // One write of M0 (the LDS base of this wavefront's stripes) serves all loads of a tile:
+  // every further write of M0 has to wait for the loads before it.
+  auto fetch_all = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW]) __attribute__((always_inline)) {
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
         (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
-#pragma unroll
-    for (int i = i0; i < i1; ++i) dma16(rs, lds0, i * 1024, off[i]);
+    if constexpr (LPW == 4)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %5, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %5, 0 offen offset:1024 lds\n\t"
+                   "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 lds\n\t"
+                   "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 lds"
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(rs));
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs));
   };
   auto k_rsrc = [&](int2 e) { return tile_rsrc(Kh, (uint32_t)k_row_bytes, e); };
   auto v_rsrc = [&](int2 e) { return tile_rsrc(Vh, (uint32_t)v_row_bytes, e); };
-  auto fetch_k = [&](int32x4 rs, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(rs, buf, koff, i0, i1);
-  };
-  auto fetch_v = [&](int32x4 rs, uint4* buf, int i0, int i1) __attribute__((always_inline)) {
-    fetch_part(rs, buf + TILE, voff, i0, i1);
-  };
+  auto fetch_k = [&](int32x4 rs, uint4* buf) __attribute__((always_inline)) { fetch_all(rs, buf, koff); };
+  auto fetch_v = [&](int32x4 rs, uint4* buf) __attribute__((always_inline)) { fetch_all(rs, buf + TILE, voff); };
 
   // LDS addresses of this lane's operand fragments inside a tile (loop invariants).
   // K (A operand of S^T): row 32 kh + ln, logical chunk 2 s + kg.
@@ -224,7 +228,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // the row sums and O stay finite far beyond that range, and O / l does not depend on m_run.
   constexpr float kSumMax = 1.0e30f;
   float m_run = -1.0e30f, l_run = 0.0f;
-  constexpr int H1 = (LPW + 1) / 2;  // loads issued in the first of the two slots of a phase
 
   // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
   // an id outside [0, n_k) becomes an empty block (count 0).
@@ -247,9 +250,9 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
     int2 e0 = entry(t0), e1 = entry(min(t0 + 1, t1 - 1)), e2 = entry(min(t0 + 2, t1 - 1));
-    fetch_k(k_rsrc(e0), buf0, 0, LPW);
-    fetch_v(v_rsrc(e0), buf0, 0, LPW);
-    fetch_k(k_rsrc(e1), buf1, 0, LPW);
+    fetch_k(k_rsrc(e0), buf0);
+    fetch_v(v_rsrc(e0), buf0);
+    fetch_k(k_rsrc(e1), buf1);
 
     // S^T[kv, q] of this wavefront's 32 KV rows x 32 query rows, from the K tile in `kt`.
     auto s_half = [&](const uint4* kt, f32x16 acc, int s0) __attribute__((always_inline)) {
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of K_{t+1}, V_t has landed
       lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
       const int32x4 krs = k_rsrc(e2), vrs = v_rsrc(e1);
-      fetch_k(krs, cur, 0, H1);
+      fetch_v(vrs, other);
       // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
       if (cnt < 64) {
 #pragma unroll
@@ -305,7 +308,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         }
       };
       softmax();
-      fetch_k(krs, cur, H1, LPW);
+      fetch_k(krs, cur);
       snext = s_half(other, snext, KS / 2);
       // Rare: the row sum says the reference is far too low (or was never set).  Then the
       // maxima are taken, the reference moves up to them and P^T is made again.
@@ -327,7 +330,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         softmax();
       }
       l_run = l_new;
-      fetch_v(vrs, other, 0, H1);
 
       // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
       // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
@@ -342,7 +344,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
           oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[mb], 0, 0, 0);
         }
       }
-      fetch_v(vrs, other, H1, LPW);
       sacc = snext;
       e0 = e1;
       e1 = e2;
