@@ -306,6 +306,37 @@ def test_calls_are_deterministic(gpu):
     assert torch.equal(i1, i2) and torch.equal(o1.view(torch.int16), o2.view(torch.int16))
 
 
+@pytest.mark.parametrize("frame_len,head_dim", [(129, 128), (400, 128), (200, 64)])
+def test_nothing_is_read_or_written_outside_the_tensors(gpu, frame_len, head_dim):
+    """The last block of a frame is short, and the last frame ends the cache.  Every tensor is
+    placed in a buffer whose surroundings hold NaN: a read past a short block or past the end of
+    the cache would poison the output (0 * NaN), a write outside O would change a guard."""
+    torch, lf = gpu
+    w = synth.small_ragged(frame_len=frame_len, chunk_idx=3, heads=2, head_dim=head_dim)
+    x = synth.make_inputs(w)
+    plain = [_dev(torch, x[k]) for k in "QKV"]
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    idx0 = lf.lf_select_mask(plain[0], plain[1], w.frame_len, w.block, b)
+    out0 = lf.lf_sparse_attn(*plain, idx0, w.frame_len, w.block)
+    pad = 64 * head_dim * 2   # one full tile of elements before and after
+
+    def guarded(t):
+        buf = torch.full((t.numel() + 2 * pad,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        view = buf[pad:pad + t.numel()].view(t.shape)
+        view.copy_(t)
+        return buf, view
+
+    (_, Q), (_, K), (_, V) = (guarded(t) for t in plain)
+    obuf, Oview = guarded(torch.zeros_like(plain[0]))
+    idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=Oview)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx0)
+    assert torch.isfinite(Oview.float()).all()
+    assert torch.equal(Oview.view(torch.int16), out0.view(torch.int16))
+    assert torch.isnan(obuf[:pad].float()).all() and torch.isnan(obuf[pad + Oview.numel():].float()).all()
+
+
 def test_binding_rejects_bad_arguments(gpu):
     torch, lf = gpu
     w = synth.cfg_tiny()
