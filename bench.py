@@ -217,6 +217,8 @@ def main():
     ap.add_argument("--no-cached-select", action="store_true",
                     help="skip the pooled-key-cache variant of the selection (keeps profiles to the "
                          "four kernels of the main path)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip timing the step as one captured HIP graph")
     ap.add_argument("--cold", action="store_true",
                     help="also time one step right after streaming a 1 GiB buffer through the caches")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -352,6 +354,20 @@ def main():
         res["select_cached"] = {"ms": float(c_ms.mean()), "ms_median_min": [float(np.median(c_ms)), float(c_ms.min())],
                                 "bytes": c_bytes, "achieved": c_bytes / (c_ms.mean() * 1e-3) / 1e9,
                                 "unit": "GB/s", "lists_equal_uncached": bool(torch.equal(idx_c, idx))}
+    if not args.no_graph:
+        # The same step (budget on the host, four kernels) captured once and replayed: what a
+        # caller that fixes its buffers pays without the per-launch host work.
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        res["graph_replay"] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / args.steps}
     if cold is not None:
         res["cold_after_1gib_stream"] = cold
     if not args.no_measured_peaks:

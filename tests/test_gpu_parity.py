@@ -337,6 +337,46 @@ def test_nothing_is_read_or_written_outside_the_tensors(gpu, frame_len, head_dim
     assert torch.isnan(obuf[:pad].float()).all() and torch.isnan(obuf[pad + Oview.numel():].float()).all()
 
 
+def test_step_replays_from_a_captured_graph(gpu):
+    """Selection + attention captured once into a HIP graph (no allocation, memset or
+    synchronisation inside the library) and replayed on new inputs written into the same
+    buffers, with eager work and synchronisations between the replays; every replay must
+    equal the eager result bit for bit."""
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=4)
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    xs = [synth.make_inputs(synth.small_ragged(chunk_idx=4, seed=s)) for s in (11, 12, 13)]
+    Q, K, V = (_dev(torch, xs[0][k]).clone() for k in "QKV")
+    sh = lf.make_shape(Q, K, frame_len=w.frame_len, block=w.block)
+    ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+    nq = w.frames_per_chunk * w.blocks_per_frame
+    idx = torch.empty((w.heads, nq, b.list_len), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(Q)
+
+    def step():
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, b, indices=idx, workspace=ws)
+        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for x in xs[1:] + xs[:1] + xs[1:2]:
+        for t, k in ((Q, "Q"), (K, "K"), (V, "V")):
+            t.copy_(_dev(torch, x[k]))
+        idx.fill_(-7)
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got_idx, got_out = idx.clone(), out.clone()
+        want_idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+        want_out = lf.lf_sparse_attn(Q, K, V, want_idx, w.frame_len, w.block)
+        torch.cuda.synchronize()
+        assert torch.equal(got_idx, want_idx)
+        assert torch.equal(got_out.view(torch.int16), want_out.view(torch.int16))
+
+
 def test_binding_rejects_bad_arguments(gpu):
     torch, lf = gpu
     w = synth.cfg_tiny()
