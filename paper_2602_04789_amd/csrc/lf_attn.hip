@@ -6,7 +6,7 @@
 // of one overlaps the vector ALU of the other.  For each listed KV block the 64 x d K and V
 // tiles are brought into a double-buffered LDS tile by asynchronous global->LDS loads, a
 // wavefront's share of a tile in one group (V of the next tile right after the barrier, K of
-// the tile after that in the middle of the step).  Wavefront
+// the tile after that after the first half of the score product).  Wavefront
 // (rh, kh) owns query rows [32 rh, 32 rh + 32) and KV rows [32 kh, 32 kh + 32) of every tile
 // and keeps its own online-softmax state (m, l, O), so nothing crosses wavefronts inside
 // the loop; the two KV halves are merged once at the end.
@@ -289,6 +289,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         }
       }
       f32x16 snext = s_half(other, zero16, 0);
+      fetch_k(krs, cur);
       // P^T = exp2(s c - m_run), packed to bfloat16 in the
       // B-operand layout of the second product; row sums from the packed values.
       bf16x8 pf[2];
@@ -308,7 +309,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
         }
       };
       softmax();
-      fetch_k(krs, cur);
       snext = s_half(other, snext, KS / 2);
       // Rare: the row sum says the reference is far too low (or was never set).  Then the
       // maxima are taken, the reference moves up to them and P^T is made again.
