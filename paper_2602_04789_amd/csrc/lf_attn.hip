@@ -98,7 +98,8 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   if (w >= a.total_wg) return;
   const int h = w / a.n_q, r = w % a.n_q;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
   const int rh = wave & 1, kh = wave >> 1;
   const int ln = lane & 31, kg = lane >> 5;
 
