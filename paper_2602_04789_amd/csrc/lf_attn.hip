@@ -1,15 +1,17 @@
 // Blockwise sparse attention for gfx950 (Eq. 13; Eq. 3 and the paragraph after it: only
 // listed tiles are computed, the element mask is never materialised).
 //
-// One workgroup (4 wavefronts) per (head, query block of 64 rows); two workgroups share a
-// compute unit, so every SIMD holds two wavefronts in different phases and the matrix core
-// of one overlaps the vector ALU of the other.  For each listed KV block the 64 x d K and V
-// tiles are brought into a double-buffered LDS tile by asynchronous global->LDS loads, a
-// wavefront's share of a tile in one group (V of the next tile right after the barrier, K of
-// the tile after that after the first half of the score product).  Wavefront
-// (rh, kh) owns query rows [32 rh, 32 rh + 32) and KV rows [32 kh, 32 kh + 32) of every tile
-// and keeps its own online-softmax state (m, l, O), so nothing crosses wavefronts inside
-// the loop; the two KV halves are merged once at the end.
+// One workgroup of two wavefronts per (head, query block of 64 rows), wavefront rh owning
+// query rows [32 rh, 32 rh + 32) with its own online-softmax state (m, l, O): nothing crosses
+// wavefronts, and there is no merge at the end.  Four workgroups share a compute unit, so
+// every SIMD holds two wavefronts of different workgroups, free to be in different parts of
+// their step (the matrix core of one beside the vector ALU of the other); the fewer
+// wavefronts a barrier ties together, the better that works (eight per workgroup measured
+// 9-13 % slower than four, two faster again).  Each listed KV block is taken as two half
+// tiles of 32 KV rows: the 32 x d K and V half tiles are brought into a double-buffered LDS
+// stage by asynchronous global->LDS loads, a wavefront's share of a half tile in one group
+// (V of the next step right after the barrier, K of the step after that after the first
+// half of the score product).
 //
 // The products are computed transposed, S^T = K Q^T and O^T = V^T P^T, with
 // v_mfma_f32_32x32x16_bf16: in the 32x32 accumulator layout a lane then holds one query
@@ -32,7 +34,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int int32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 128;
 constexpr int kMaxEnt = 512;  // list entries decoded per pass (power of two)
 
 struct AttnArgs {
@@ -79,18 +81,17 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
   constexpr int CH = D / 8;                 // 16-byte chunks per token row
   constexpr int KS = D / 16;                // k-steps of S^T = K Q^T
   constexpr int MB = D / 32;                // 32-row blocks of O^T
   constexpr int RPI = 64 / CH;              // tile rows one wavefront load instruction covers
-  constexpr int LPW = 64 / (RPI * 4);       // load instructions per wavefront, per tile, per tensor
-  constexpr int TILE = 64 * CH;             // uint4 per tile
+  constexpr int LPW = 32 / (RPI * 2);       // load instructions per wavefront, per tile, per tensor
+  constexpr int TILE = 32 * CH;             // uint4 per half tile (32 KV rows)
 
   __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles; reused for the final merge
   __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
-  __shared__ float ml[2][2][64];
-  __shared__ int2 ent[kMaxEnt];             // (first token, token count) per list entry
+  __shared__ int2 ent[kMaxEnt];             // (first token, token count <= 32) per half tile
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
-  const int rh = wave & 1, kh = wave >> 1;
+  const int rh = wave;
   const int ln = lane & 31, kg = lane >> 5;
 
   const int qtok0 = (r / a.nb) * a.n + (r % a.nb) * 64;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   // The list entries of the first pass are requested first, so that they travel together with
   // the Q fragments instead of after them.
   const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
-  constexpr int EPT = kMaxEnt / kThreads;   // list entries per thread and pass
+  constexpr int EPT = kMaxEnt / 2 / kThreads;   // list entries per thread and pass (two half tiles each)
   int pre[EPT];
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
@@ -192,11 +193,11 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   auto fetch_v = [&](int32x4 rs, uint4* buf) __attribute__((always_inline)) { fetch_all(rs, buf + TILE, voff); };
 
   // LDS addresses of this lane's operand fragments inside a tile (loop invariants).
-  // K (A operand of S^T): row 32 kh + ln, logical chunk 2 s + kg.
+  // K (A operand of S^T): row ln of the half tile, logical chunk 2 s + kg.
   int kaddr[KS];
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
-    const int row = 32 * kh + ln;
+    const int row = ln;
     kaddr[s] = row * CH + k_swz<CH>(row, 2 * s + kg);
   }
   // V^T (A operand of O^T) through the transposing LDS read: within each group of 16 lanes,
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   int vbase[MB];
   {
     const int i16 = lane & 15;
-    const int tr_row = 32 * kh + 4 * kg + (i16 >> 2);
+    const int tr_row = 4 * kg + (i16 >> 2);
     const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -230,24 +231,28 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
   constexpr float kSumMax = 1.0e30f;
   float m_run = -1.0e30f, l_run = 0.0f;
 
-  // Lists are decoded kMaxEnt entries at a time into LDS: block id -> (first token, count);
-  // an id outside [0, n_k) becomes an empty block (count 0).
-  for (int t0 = 0; t0 < a.list_len; t0 += kMaxEnt) {
-    const int t1 = min(a.list_len, t0 + kMaxEnt);
+  // Lists are decoded kMaxEnt / 2 entries at a time into LDS: block id -> two half tiles
+  // (first token, count); an id outside [0, n_k) becomes two empty ones (count 0).
+  for (int l0 = 0; l0 < a.list_len; l0 += kMaxEnt / 2) {
+    const int l1 = min(a.list_len, l0 + kMaxEnt / 2);
+    const int t0 = 2 * l0, t1 = 2 * l1;   // half-tile steps of this pass
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      const int i = t0 + tid + e * kThreads;
-      if (i < t1) {
-        const int c = t0 == 0 ? pre[e] : list[i];
+      const int i = l0 + tid + e * kThreads;
+      if (i < l1) {
+        const int c = l0 == 0 ? pre[e] : list[i];
         const bool ok = (unsigned)c < (unsigned)a.n_k;
         const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
-        ent[i - t0] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+        const int cnt = ok ? min(64, a.n - j * 64) : 0;
+        ent[2 * (i - l0)] = make_int2(tau * a.n + j * 64, min(cnt, 32));
+        ent[2 * (i - l0) + 1] = make_int2(tau * a.n + j * 64 + 32, max(cnt - 32, 0));
       }
     }
     __syncthreads();
-    // Software pipeline, one tile deep: iteration t computes S^T of tile t+1 (matrix core)
+    // Software pipeline, one step deep (a step, "tile" below, is one half tile of 32 KV rows):
+    // iteration t computes S^T of tile t+1 (matrix core)
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
     int2 e0 = entry(t0), e1 = entry(min(t0 + 1, t1 - 1)), e2 = entry(min(t0 + 2, t1 - 1));
@@ -281,11 +286,11 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
       lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
       const int32x4 krs = k_rsrc(e2), vrs = v_rsrc(e1);
       fetch_v(vrs, other);
-      // accumulator i of a lane: KV row 32 kh + 8 (i/4) + 4 kg + i%4, query column ln
-      if (cnt < 64) {
+      // accumulator i of a lane: KV row 8 (i/4) + 4 kg + i%4 of the half tile, query column ln
+      if (cnt < 32) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int kv = 32 * kh + 8 * (i >> 2) + 4 * kg + (i & 3);
+          const int kv = 8 * (i >> 2) + 4 * kg + (i & 3);
           if (kv >= cnt) sacc[i] = -INFINITY;
         }
       }
@@ -356,45 +361,23 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_kernel(AttnArgs a) {
     };
     for (int t = t0; t < t1; t += 2) {
       tile(t, buf0, buf1);
-      if (t + 1 < t1) tile(t + 1, buf1, buf0);
+      tile(t + 1, buf1, buf0);
     }
   }
 
-  // Merge the two KV halves through LDS (the 32 KiB of the even-tile buffer hold both query
-  // halves): wavefronts with kh = 1 publish (m, l, O^T), those with kh = 0 combine and store.
+  // Every wavefront owns its 32 query rows completely: normalise and store.
   l_run += __shfl_xor(l_run, 32);
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  float* mbuf = reinterpret_cast<float*>(buf0) + rh * (MB * 16 * 64);  // [MB*16][64] per query half
-  __syncthreads();
-  if (kh == 1) {
-    ml[rh][0][lane] = m_run;
-    ml[rh][1][lane] = l_run;
+  const float inv = 1.0f / l_run;
+  if (qrow < q_cnt) {
+    uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mbuf[(mb * 16 + i) * 64 + lane] = oacc[mb][i];
-  }
-  __syncthreads();
-  if (kh == 0) {
-    const float m2 = ml[rh][0][lane], l2 = ml[rh][1][lane];
-    const float m = fmaxf(m_run, m2);
-    const float a1 = __builtin_amdgcn_exp2f(m_run - m), a2 = __builtin_amdgcn_exp2f(m2 - m);
-    const float inv = 1.0f / (l_run * a1 + l2 * a2);
-    if (qrow < q_cnt) {
-      uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 o4;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 o4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int i = 4 * g + e;
-            const float o2 = mbuf[(mb * 16 + i) * 64 + lane];
-            o4[e] = (__bf16)((oacc[mb][i] * a1 + o2 * a2) * inv);
-          }
-          *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
-        }
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[mb][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
       }
     }
   }
