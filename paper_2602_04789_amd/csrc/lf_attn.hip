@@ -340,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
       // O^T[d, q] += V^T[d, kv] P^T[kv, q]; k-step u takes accumulators 8u .. 8u+7, i.e.
       // KV rows 16u + 4kg + {0..3} and 16u + 8 + 4kg + {0..3} of this wavefront's half.
       // The second product runs at low priority, the score/softmax part at high priority: with
-      // two wavefronts per SIMD this keeps them in different parts of the step (measured -1.7 %).
+      // two wavefronts per SIMD this helps to keep them in different parts of the step.
       __builtin_amdgcn_s_setprio(0);
       const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(cur + TILE);
 #pragma unroll
