@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
 
   __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles; reused for the final merge
   __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
-  __shared__ int2 ent[kMaxEnt];             // (first token, token count <= 32) per half tile
+  __shared__ int2 ent[kMaxEnt / 2];         // (first token, token count) per list entry of a pass
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -152,10 +152,13 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
     voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + (uint32_t)v_swz<CH>(row, ld_p) * 16u - 1024u * i;
   }
   // (first token, token count) of list entry t, wavefront-uniform.
-  auto entry = [&](int t) -> int2 {
-    const int2 e = ent[t & (kMaxEnt - 1)];
+  auto entry = [&](int i) -> int2 {
+    const int2 e = ent[i & (kMaxEnt / 2 - 1)];
     return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
   };
+  // the two half tiles of a list entry: 32 rows each, the second starts 32 tokens further
+  auto lower = [](int2 e) { return make_int2(e.x, min(e.y, 32)); };
+  auto upper = [](int2 e) { return make_int2(e.x + 32, max(e.y - 32, 0)); };
   // The loads are raw buffer loads whose resource is the tile itself: base = the block's
   // first token, num_records = its token count x the row pitch.  Rows past a short block's
   // count are then out of range, which touches no memory and writes zeros, so the loads need
@@ -246,8 +249,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
         const bool ok = (unsigned)c < (unsigned)a.n_k;
         const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
         const int cnt = ok ? min(64, a.n - j * 64) : 0;
-        ent[2 * (i - l0)] = make_int2(tau * a.n + j * 64, min(cnt, 32));
-        ent[2 * (i - l0) + 1] = make_int2(tau * a.n + j * 64 + 32, max(cnt - 32, 0));
+        ent[i - l0] = make_int2(tau * a.n + j * 64, cnt);
       }
     }
     __syncthreads();
@@ -255,7 +257,9 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
     // iteration t computes S^T of tile t+1 (matrix core)
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
-    int2 e0 = entry(t0), e1 = entry(min(t0 + 1, t1 - 1)), e2 = entry(min(t0 + 2, t1 - 1));
+    const int2 eb0 = entry(l0);
+    int2 eb = entry(min(l0 + 1, l1 - 1));   // list entry whose half tiles are requested next
+    int2 e0 = lower(eb0), e1 = upper(eb0), e2 = lower(eb);
     fetch_k(k_rsrc(e0), buf0);
     fetch_v(v_rsrc(e0), buf0);
     fetch_k(k_rsrc(e1), buf1);
@@ -280,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
 
     // Past the end of the list the pipeline runs on the last entry again: its loads and its
     // S^T are redundant and unused, which keeps the loop body free of branches.
-    auto tile = [&](int t, uint4* cur, uint4* other) __attribute__((always_inline)) {
+    auto tile = [&](int t, uint4* cur, uint4* other, bool second) __attribute__((always_inline)) {
       const int cnt = e0.y;
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of K_{t+1}, V_t has landed
       lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
@@ -357,11 +361,16 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
       sacc = snext;
       e0 = e1;
       e1 = e2;
-      e2 = entry(min(t + 3, t1 - 1));
+      if (second) {          // step t + 3 opens the next list entry
+        eb = entry(min((t + 3) >> 1, l1 - 1));
+        e2 = lower(eb);
+      } else {
+        e2 = upper(eb);
+      }
     };
     for (int t = t0; t < t1; t += 2) {
-      tile(t, buf0, buf1);
-      tile(t + 1, buf1, buf0);
+      tile(t, buf0, buf1, false);
+      tile(t + 1, buf1, buf0, true);
     }
   }
 
