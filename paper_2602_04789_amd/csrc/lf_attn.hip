@@ -320,6 +320,16 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
       };
       softmax();
       snext = s_half(other, snext, KS / 2);
+      // The V^T fragments of the first k-step are requested before the branch below, so that
+      // the second product does not start by waiting for LDS.
+      const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(cur + TILE);
+      bf16x8 vf0[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(0, 0, mb)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(0, 1, mb)));
+        vf0[mb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
       // Rare: the row sum says the reference is far too low (or was never set).  Then the
       // maxima are taken, the reference moves up to them and P^T is made again.
       if (__ballot(l_new > kSumMax) != 0ull) {
@@ -346,16 +356,15 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
       // The second product runs at low priority, the score/softmax part at high priority: with
       // two wavefronts per SIMD this helps to keep them in different parts of the step.
       __builtin_amdgcn_s_setprio(0);
-      const uint16_t* Vs16 = reinterpret_cast<const uint16_t*>(cur + TILE);
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int mb = 0; mb < MB; ++mb)
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0[mb], pf[0], oacc[mb], 0, 0, 0);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 0, mb)));
-          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 1, mb)));
-          const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[mb], 0, 0, 0);
-        }
+      for (int mb = 0; mb < MB; ++mb) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(1, 0, mb)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(1, 1, mb)));
+        const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1], oacc[mb], 0, 0, 0);
       }
       __builtin_amdgcn_s_setprio(3);
       sacc = snext;
