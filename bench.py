@@ -38,7 +38,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # the same run shows, WRITE_SIZE by 1.000): profiles/last_chunk_pmc_counters.txt.
 # None for workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("last_chunk", "attn"): (258200 * 1.994 + 14040) * 1024,
+    ("last_chunk", "attn"): (266600 * 1.994 + 14040) * 1024,
     ("last_chunk", "select"): ((56190 + 1454 + 8668) * 1.994 + (6752 + 180 + 675)) * 1024,
 }
 
