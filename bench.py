@@ -357,17 +357,20 @@ def main():
     if not args.no_graph:
         # The same step (budget on the host, four kernels) captured once and replayed: what a
         # caller that fixes its buffers pays without the per-launch host work.
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            step()
-        for _ in range(3):
-            g.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            g.replay()
-        torch.cuda.synchronize()
-        res["graph_replay"] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / args.steps}
+        try:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step()
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            res["graph_replay"] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / args.steps}
+        except RuntimeError as exc:   # an extra: the headline numbers above do not depend on it
+            res["graph_replay"] = {"ms_per_step": None, "error": str(exc)[:200]}
     if cold is not None:
         res["cold_after_1gib_stream"] = cold
     if not args.no_measured_peaks:
