@@ -113,6 +113,10 @@ SMALL = {
     "aligned_1536_c3": lambda: synth.scaled(synth.cfg_paper_5s(3, heads=2)),
     "one_token_tail": lambda: synth.small_ragged(frame_len=129, chunk_idx=3, heads=2),
     "short_frame": lambda: synth.small_ragged(frame_len=40, chunk_idx=5, heads=2, k_frames=1),
+    # last block of 31, 32 and 33 tokens: around the 32-row half tiles of the attention kernel
+    "tail_31": lambda: synth.small_ragged(frame_len=95, chunk_idx=3, heads=2),
+    "tail_32": lambda: synth.small_ragged(frame_len=96, chunk_idx=3, heads=2),
+    "tail_33": lambda: synth.small_ragged(frame_len=97, chunk_idx=3, heads=2, head_dim=64),
     "many_frames": lambda: synth.small_ragged(frame_len=64, chunk_idx=40, frames_per_chunk=2,
                                               heads=1, k_frames=5, n_sink=2, n_win=3),
     # candidate sets wider than one per thread: 320, 560 and 1040 candidate blocks
