@@ -143,7 +143,12 @@ def chunk_budget(chunk_idx: int, sched) -> Budget:
     cur_mand = 1 if (sched.current_mandatory and F_h > 0) else 0
     n_tf = n_sink + n_win + k_frames                # selected history frames
     n_cand = n_tf * nb + (0 if cur_mand else f * nb)  # |B_r|
-    rho = min(max(keep_ratio(chunk_idx, sched), 0.0), 1.0)
+    rho = keep_ratio(chunk_idx, sched)
+    if not (0.0 <= rho <= 1.0):
+        # Reading: s_i of Eq. 5 is a sparsity *ratio*; parameters that push it outside [0, 1]
+        # (e.g. s_base 0.5, s_target 0.1 over 7 chunks gives s_2 < 0) define no schedule of the
+        # method, and the paper gives no rule for them, so they are rejected, not altered.
+        raise ValueError(f"keep ratio {rho} of chunk {chunk_idx} is outside [0, 1]")
     if sched.ratio_of == OF_CANDIDATES:
         k_blocks = _ceil_count(rho, n_cand)
     elif sched.ratio_of == OF_HISTORY:

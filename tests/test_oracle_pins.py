@@ -124,6 +124,28 @@ def test_candidate_count_and_activation_rule(row):
             assert b.list_len == min(want, (kept_hist + f) * 24)
 
 
+@pytest.mark.parametrize("row", _rows("cag_list_len.txt"), ids=lambda r: f"{r[0]}-{r[1]}")
+def test_budget_counts_of_the_papers_operating_points(row):
+    """Keep-counts worked out by hand from Eq. 5-6 and the appendix table (golden file)."""
+    setting, chunk, k_blocks = row[0], int(row[1]), int(row[2])
+    w = (synth.cfg_paper_5s if setting == "5s" else synth.cfg_paper_15s)(chunk)
+    b = O.chunk_budget(chunk, w.schedule)
+    assert (b.k_blocks, b.list_len, b.current_mandatory) == (k_blocks, k_blocks, 0)
+
+
+def test_schedule_leaving_the_unit_interval_is_rejected():
+    """Eq. 5 with s_base 0.5 / s_target 0.1 over 7 chunks: beta = 0.4 * 27 / 12.4776 = 0.8655,
+    s_2 = 0.5 - 0.8655 / sqrt(2) = -0.112 -- not a sparsity ratio.  In-range chunks of the same
+    schedule (s_7 = 0.173) are still served."""
+    sch = synth.Schedule(mode=synth.SCHED_CAG, n_chunks=7, frame_len=1536, ratio_of=synth.OF_ALL,
+                         current_mandatory=0, first_chunk_dense=1, s_base=0.5, s_target=0.1)
+    assert O.cag_sparsity(2, 7, 0.5, 0.1) < 0.0 < O.cag_sparsity(7, 7, 0.5, 0.1)
+    with pytest.raises(ValueError):
+        O.chunk_budget(2, sch)
+    b = O.chunk_budget(7, sch)
+    assert b.k_blocks == min(math.ceil((1 - (0.5 - 0.8655369 / math.sqrt(7))) * 7 * 72), 216)
+
+
 # ----------------------------------------------------------------------------- pooling (Eq. 7)
 
 def test_block_sums_are_exact_integer_arithmetic():
