@@ -45,7 +45,7 @@ typedef enum {
   LF_ERR_DTYPE = -4,     /* dtype other than LF_BF16 */
   LF_ERR_ALIGN = -5,     /* pointer or stride breaks the 16-byte row alignment */
   LF_ERR_WORKSPACE = -6, /* workspace NULL or smaller than lf_workspace_bytes() */
-  LF_ERR_HIP = -7,       /* a HIP launch failed (hipGetLastError() was not hipSuccess) */
+  LF_ERR_HIP = -7,       /* a kernel launch of this call failed */
   LF_ERR_SCHEDULE = -8   /* schedule fields out of range */
 } lf_status;
 
@@ -131,10 +131,13 @@ typedef struct {
  *   sum(alpha_i w_i) over i = 2..n_chunks; chunk 1 keeps everything.
  * counts: n_sink, n_win, k_frames clamped to the history as documented in lf_budget;
  *   |B_r| = (n_sink + n_win + k_frames)*nb (+ f*nb when the current chunk competes);
- *   k_blocks = ceil(rho_i * N - 1e-9) with N per ratio_of (for LF_OF_ALL with a mandatory
- *   current chunk the f*nb current blocks are subtracted), clamped to [min(1,|B_r|), |B_r|].
+ *   k_blocks = the smallest integer >= rho_i * N, a product within 1e-9 above an integer
+ *   counting as that integer, with N per ratio_of (for LF_OF_ALL with a mandatory current
+ *   chunk the f*nb current blocks are subtracted), clamped to [min(1,|B_r|), |B_r|].
  * Errors: LF_ERR_NULL; LF_ERR_SCHEDULE (chunk_idx < 1, non-positive sizes, negative counts,
- *   ratios outside [0, 1], unknown mode / ratio_of).
+ *   ratios outside [0, 1], unknown mode / ratio_of, or a Chunk-Aware Growth schedule whose
+ *   s_i of Eq. 5 leaves [0, 1] at this chunk: s_i is a sparsity ratio and such parameters are
+ *   rejected, not clamped).
  */
 int lf_chunk_budget(int32_t chunk_idx, const lf_schedule* schedule, lf_budget* budget);
 
@@ -178,7 +181,8 @@ int lf_workspace_layout(const lf_shape* shape, const lf_budget* budget, size_t o
  *   workspace     device scratch of >= lf_workspace_bytes(), 256-byte aligned.
  * Errors: LF_ERR_NULL, LF_ERR_SHAPE, LF_ERR_DTYPE, LF_ERR_ALIGN, LF_ERR_BUDGET (counts
  *   negative, exceeding their candidate sets, list_len inconsistent, more than 2048
- *   candidate blocks or 1024 candidate frames), LF_ERR_WORKSPACE, LF_ERR_HIP.
+ *   candidate blocks, 1024 candidate frames, 4096 history frames or 1024 frames per chunk),
+ *   LF_ERR_WORKSPACE, LF_ERR_HIP.
  */
 int lf_select_mask(const void* Q, const void* Kcache, const lf_shape* shape,
                    const lf_budget* budget, int32_t* indices, void* workspace,
@@ -193,8 +197,8 @@ int lf_select_mask(const void* Q, const void* Kcache, const lf_shape* shape,
  * Arguments
  *   Q, Kcache, Vcache  device, bfloat16, layout above.
  *   indices            device, int32 [H][n_q][list_len]; ids outside [0, n_k) are skipped;
- *                      order is free, duplicates count twice.  list_len >= 1 and every list
- *                      must hold at least one valid id.
+ *                      order is free, duplicates count twice.  list_len >= 1; the rows of a
+ *                      query block whose list holds no valid id are written as zeros.
  *   softmax_scale      0 selects 1/sqrt(d).
  *   O                  device, bfloat16 [H][q_len][d] with the o_ strides, written.
  * Errors: LF_ERR_NULL, LF_ERR_SHAPE, LF_ERR_DTYPE, LF_ERR_ALIGN, LF_ERR_BUDGET

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
   constexpr int LPW = 32 / (RPI * 2);       // load instructions per wavefront, per tile, per tensor
   constexpr int TILE = 32 * CH;             // uint4 per half tile (32 KV rows)
 
-  __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles; reused for the final merge
+  __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles
   __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
   __shared__ int2 ent[kMaxEnt / 2];         // (first token, token count) per list entry of a pass
 
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
 
   // Every wavefront owns its 32 query rows completely: normalise and store.
   l_run += __shfl_xor(l_run, 32);
-  const float inv = 1.0f / l_run;
+  const float inv = l_run > 0.0f ? 1.0f / l_run : 0.0f;   // a list without a valid id gives zero rows
   if (qrow < q_cnt) {
     uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
@@ -430,9 +430,7 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
   a.c = scale * 1.4426950408889634f;
   const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
   hipStream_t st = (hipStream_t)stream;
-  if (dm->d == 128)
-    hipLaunchKernelGGL(lf_attn_kernel<128>, dim3(grid), dim3(kThreads), 0, st, a);
-  else
-    hipLaunchKernelGGL(lf_attn_kernel<64>, dim3(grid), dim3(kThreads), 0, st, a);
-  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+  const hipError_t rc = dm->d == 128 ? lf_launch(lf_attn_kernel<128>, dim3(grid), dim3(kThreads), 0, st, a)
+                                     : lf_launch(lf_attn_kernel<64>, dim3(grid), dim3(kThreads), 0, st, a);
+  return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
 }

@@ -10,6 +10,9 @@
 #define LF_MAX_CAND_BLOCKS 2048  // |B_r| the selection kernel can rank in LDS
 #define LF_MAX_CAND_FRAMES 1024  // |M| the selection kernel can rank in LDS
 #define LF_MAX_HIST_FRAMES 4096  // F_h bound (flag array in LDS)
+#define LF_MAX_CHUNK_FRAMES 1024 // f bound: with the three above it keeps the selection kernel's
+                                 // dynamic LDS below 64 KiB, so the size is known to fit
+                                 // before anything is enqueued
 
 // Derived sizes of one call; filled by lf_derive() after validation.
 struct lf_dims {
@@ -33,5 +36,17 @@ int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int m
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
                    const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
                    void* O, void* stream);
+
+#ifdef __HIPCC__
+#include <hip/hip_runtime.h>
+// Launches a kernel and returns this launch's own status (an error left behind by the caller's
+// earlier work is neither reported nor cleared).
+template <typename... KArgs, typename... Args>
+inline hipError_t lf_launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes,
+                            hipStream_t stream, Args... args) {
+  void* argv[] = {(void*)&args...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, lds_bytes, stream);
+}
+#endif
 
 #endif

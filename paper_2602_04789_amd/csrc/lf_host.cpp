@@ -11,37 +11,58 @@ namespace {
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// beta of Eq. 6 with alpha_i = 1/sqrt(i) and chunk weights l^q_i l^k_i d proportional to i.
-double cag_beta(int n_chunks, double s_base, double s_target) {
-  if (n_chunks < 2) return 0.0;
-  double num = 0.0, den = 0.0;
-  for (int i = 2; i <= n_chunks; ++i) {
-    num += (double)i;
-    den += (double)i / sqrt((double)i);
-  }
-  return (s_base - s_target) * num / den;
+// How the history of F_h frames splits for one chunk (footnote to Eq. 7, text after Eq. 9):
+// the earliest frames are the sink, the nearest ones the window (it takes what the sink
+// leaves), the rest is the candidate set M, of which top-k retrieves `pick` frames.
+struct HistorySplit {
+  int sink, window, candidates, pick;
+  int kept() const { return sink + window + pick; }
+};
+
+HistorySplit split_history(int F_h, const lf_schedule& sc) {
+  HistorySplit h;
+  h.sink = sc.n_sink > F_h ? F_h : sc.n_sink;
+  const int rest = F_h - h.sink;
+  h.window = sc.n_win > rest ? rest : sc.n_win;
+  h.candidates = rest - h.window;
+  h.pick = sc.k_frames > h.candidates ? h.candidates : sc.k_frames;
+  return h;
 }
 
-double keep_ratio(int i, const lf_schedule* s) {
-  if (s->first_chunk_dense && i == 1) return 1.0;
-  switch (s->mode) {
-    case LF_SCHED_FIXED:
-      return s->keep_fixed;
-    case LF_SCHED_LINEAR: {
-      if (s->n_chunks <= 1) return s->keep_first;
-      double t = (double)(i - 1) / (double)(s->n_chunks - 1);
-      return s->keep_first + (s->keep_last - s->keep_first) * t;
-    }
-    default: {  // LF_SCHED_CAG; Eq. 5 is stated for i > 1
-      if (i == 1) return 1.0;
-      double s_i = s->s_base - cag_beta(s->n_chunks, s->s_base, s->s_target) / sqrt((double)i);
-      return 1.0 - s_i;
+// Fraction of blocks chunk i keeps.  Chunk-Aware Growth (Eq. 5): s_i = s_base - beta alpha_i
+// with alpha_i = i^(-1/2); Eq. 6 with chunk weights proportional to i fixes
+//   beta = (s_base - s_target) * W / A,  W = sum_{i=2..n} i = n(n+1)/2 - 1,
+//   A = sum_{i=2..n} i^(1/2).
+// Returns false when the fraction is not a ratio (outside [0, 1]).
+bool keep_fraction(int i, const lf_schedule& sc, double* out) {
+  double keep = 1.0;
+  const bool dense = i == 1 && (sc.first_chunk_dense || sc.mode == LF_SCHED_CAG);
+  if (!dense) {
+    if (sc.mode == LF_SCHED_FIXED) {
+      keep = sc.keep_fixed;
+    } else if (sc.mode == LF_SCHED_LINEAR) {
+      const double span = sc.n_chunks > 1 ? (double)(i - 1) / (double)(sc.n_chunks - 1) : 0.0;
+      keep = sc.keep_first + span * (sc.keep_last - sc.keep_first);
+    } else {
+      const double n = (double)sc.n_chunks;
+      const double W = 0.5 * n * (n + 1.0) - 1.0;
+      double A = 0.0;
+      for (int j = 2; j <= sc.n_chunks; ++j) A += sqrt((double)j);
+      const double beta = sc.n_chunks >= 2 ? (sc.s_base - sc.s_target) * W / A : 0.0;
+      keep = 1.0 - (sc.s_base - beta / sqrt((double)i));
     }
   }
+  *out = keep;
+  return keep >= 0.0 && keep <= 1.0;
 }
 
-inline int ceil_count(double ratio, int total) {
-  return (int)ceil(ratio * (double)total - 1e-9);
+// Smallest integer count that is not below ratio * total, where products within 1e-9 of an
+// integer count as that integer (0.4 * 225 must give 90, not 91).
+inline int64_t blocks_for(double ratio, int64_t total) {
+  const double x = ratio * (double)total;
+  int64_t k = (int64_t)x;
+  if (x - (double)k > 1e-9) ++k;
+  return k;
 }
 
 inline bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }
@@ -63,43 +84,44 @@ extern "C" int lf_chunk_budget(int32_t chunk_idx, const lf_schedule* s, lf_budge
     return LF_ERR_SCHEDULE;
   if ((int64_t)(chunk_idx) * s->frames_per_chunk > (int64_t)1 << 24) return LF_ERR_SCHEDULE;
 
-  const int f = s->frames_per_chunk;
-  const int nb = ceil_div(s->frame_len, s->block);
-  const int F_h = (chunk_idx - 1) * f;
-  const int n_sink = s->n_sink < F_h ? s->n_sink : F_h;
-  const int n_win = s->n_win < F_h - n_sink ? s->n_win : F_h - n_sink;
-  const int m = F_h - n_sink - n_win;
-  const int k_frames = s->k_frames < m ? s->k_frames : m;
-  const int cur_mand = (s->current_mandatory && F_h > 0) ? 1 : 0;
-  const int64_t n_tf = (int64_t)n_sink + n_win + k_frames;
-  const int64_t n_cand64 = n_tf * nb + (cur_mand ? 0 : (int64_t)f * nb);
-  if (n_cand64 > (int64_t)1 << 30 || (int64_t)(F_h + f) * nb > (int64_t)1 << 30)
-    return LF_ERR_SCHEDULE;
-  const int n_cand = (int)n_cand64;
-  double rho = keep_ratio(chunk_idx, s);
-  if (rho < 0.0) rho = 0.0;  // CAG with extreme parameters
-  if (rho > 1.0) rho = 1.0;
-  int k_blocks;
-  if (s->ratio_of == LF_OF_CANDIDATES)
-    k_blocks = ceil_count(rho, n_cand);
-  else if (s->ratio_of == LF_OF_HISTORY)
-    k_blocks = ceil_count(rho, F_h > 0 ? F_h * nb : n_cand);
+  const int64_t f = s->frames_per_chunk;
+  const int64_t nb = ceil_div(s->frame_len, s->block);
+  const int F_h = (chunk_idx - 1) * (int)f;
+  const HistorySplit hs = split_history(F_h, *s);
+  // With no history the current blocks are the only candidates, whatever the flag says.
+  const bool current_outside_topk = s->current_mandatory && F_h > 0;
+  const int64_t current_blocks = f * nb;
+  const int64_t candidates = hs.kept() * nb + (current_outside_topk ? 0 : current_blocks);
+  if (candidates > (int64_t)1 << 30 || (F_h + f) * nb > (int64_t)1 << 30) return LF_ERR_SCHEDULE;
+
+  // Sec. 4.1: s_i is a sparsity ratio; a schedule whose Eq. 5 leaves [0, 1] at this chunk is
+  // rejected rather than altered.
+  double keep;
+  if (!keep_fraction(chunk_idx, *s, &keep)) return LF_ERR_SCHEDULE;
+
+  // The ratio is a fraction of the candidates, of the history blocks (of the candidates when
+  // there is no history), or of all KV blocks; in the last case the current blocks, when they
+  // are kept outside the top-k, come off the count.
+  int64_t k;
+  if (s->ratio_of == LF_OF_ALL)
+    k = blocks_for(keep, (F_h + f) * nb) - (current_outside_topk ? current_blocks : 0);
+  else if (s->ratio_of == LF_OF_HISTORY && F_h > 0)
+    k = blocks_for(keep, F_h * nb);
   else
-    k_blocks = ceil_count(rho, (F_h + f) * nb) - (cur_mand ? f * nb : 0);
-  if (k_blocks > n_cand) k_blocks = n_cand;
-  const int lo = n_cand < 1 ? n_cand : 1;
-  if (k_blocks < lo) k_blocks = lo;
+    k = blocks_for(keep, candidates);
+  if (k < 1) k = 1;                     // never attend to nothing ...
+  if (k > candidates) k = candidates;   // ... nor to more than there is
 
   memset(out, 0, sizeof(*out));
   out->n_hist_frames = F_h;
-  out->frames_per_chunk = f;
-  out->n_sink = n_sink;
-  out->n_win = n_win;
-  out->k_frames = k_frames;
-  out->k_blocks = k_blocks;
-  out->current_mandatory = cur_mand;
-  out->list_len = k_blocks + (cur_mand ? f * nb : 0);
-  out->keep_ratio = rho;
+  out->frames_per_chunk = (int32_t)f;
+  out->n_sink = hs.sink;
+  out->n_win = hs.window;
+  out->k_frames = hs.pick;
+  out->k_blocks = (int32_t)k;
+  out->current_mandatory = current_outside_topk ? 1 : 0;
+  out->list_len = (int32_t)(k + (current_outside_topk ? current_blocks : 0));
+  out->keep_ratio = keep;
   return LF_OK;
 }
 
@@ -148,7 +170,8 @@ int lf_derive(const lf_shape* s, const lf_budget* b, lf_dims* o) {
   o->m = o->F_h - b->n_sink - b->n_win;
   if (b->k_frames > o->m) return LF_ERR_BUDGET;
   if (b->current_mandatory != 0 && b->current_mandatory != 1) return LF_ERR_BUDGET;
-  if (o->F_h > LF_MAX_HIST_FRAMES || o->m > LF_MAX_CAND_FRAMES) return LF_ERR_BUDGET;
+  if (o->F_h > LF_MAX_HIST_FRAMES || o->m > LF_MAX_CAND_FRAMES || o->f > LF_MAX_CHUNK_FRAMES)
+    return LF_ERR_BUDGET;
   o->n_tf = b->n_sink + b->n_win + b->k_frames;
   const int64_t n_cand = (int64_t)o->n_tf * o->nb + (b->current_mandatory ? 0 : (int64_t)o->f * o->nb);
   if (n_cand > LF_MAX_CAND_BLOCKS) return LF_ERR_BUDGET;

@@ -363,7 +363,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
 
 // Pools query blocks (when Q is given) and the KV blocks of frames [frame0, frame1) into qt / the
 // quad-major matrix kt with kt_rows rows per head.
-static void launch_pool(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
+static hipError_t launch_pool(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
                         float* kt, int kt_rows, int frame0, int frame1, hipStream_t st) {
   PoolArgs pa;
   pa.Q = (const uint16_t*)Q;
@@ -381,14 +381,12 @@ static void launch_pool(const void* Q, const void* K, const lf_shape* s, const l
   pa.n_kp = (frame1 - frame0) * dm->nb;
   pa.kt_rows = kt_rows;
   const unsigned pool_grid = (unsigned)(dm->H * (pa.n_q + pa.n_kp));
-  if (pool_grid == 0) return;
-  if (dm->d == 128)
-    hipLaunchKernelGGL(lf_pool_kernel<128>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
-  else
-    hipLaunchKernelGGL(lf_pool_kernel<64>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
+  if (pool_grid == 0) return hipSuccess;
+  return dm->d == 128 ? lf_launch(lf_pool_kernel<128>, dim3(pool_grid), dim3(kThreads), 0, st, pa)
+                      : lf_launch(lf_pool_kernel<64>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
 }
 
-static void launch_select(const lf_budget* b, const lf_dims* dm, const float* qt, const float* kt,
+static hipError_t launch_select(const lf_budget* b, const lf_dims* dm, const float* qt, const float* kt,
                           const float* kh, int kt_rows, int kh_rows, int kh_row0, int32_t* indices,
                           hipStream_t st) {
   SelectArgs sa;
@@ -420,14 +418,17 @@ static void launch_select(const lf_budget* b, const lf_dims* dm, const float* qt
   const unsigned sel_grid = (unsigned)(dm->H * dm->n_q);
   const size_t lds = select_lds_bytes(sa, e);
 #define LF_LAUNCH_SELECT(DD, EE) \
-  hipLaunchKernelGGL((lf_select_kernel<DD, EE>), dim3(sel_grid), dim3(kThreads), lds, st, sa)
+  lf_launch(lf_select_kernel<DD, EE>, dim3(sel_grid), dim3(kThreads), lds, st, sa)
   if (dm->d == 128) {
-    if (e == 1) LF_LAUNCH_SELECT(128, 1); else if (e == 2) LF_LAUNCH_SELECT(128, 2);
-    else if (e == 4) LF_LAUNCH_SELECT(128, 4); else LF_LAUNCH_SELECT(128, 8);
-  } else {
-    if (e == 1) LF_LAUNCH_SELECT(64, 1); else if (e == 2) LF_LAUNCH_SELECT(64, 2);
-    else if (e == 4) LF_LAUNCH_SELECT(64, 4); else LF_LAUNCH_SELECT(64, 8);
+    if (e == 1) return LF_LAUNCH_SELECT(128, 1);
+    if (e == 2) return LF_LAUNCH_SELECT(128, 2);
+    if (e == 4) return LF_LAUNCH_SELECT(128, 4);
+    return LF_LAUNCH_SELECT(128, 8);
   }
+  if (e == 1) return LF_LAUNCH_SELECT(64, 1);
+  if (e == 2) return LF_LAUNCH_SELECT(64, 2);
+  if (e == 4) return LF_LAUNCH_SELECT(64, 4);
+  return LF_LAUNCH_SELECT(64, 8);
 #undef LF_LAUNCH_SELECT
 }
 
@@ -438,13 +439,14 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
   float* qt = (float*)(ws + dm->off_qt);
   float* kt = (float*)(ws + dm->off_kt);
   float* kh = (float*)(ws + dm->off_kh);
-  launch_pool(Q, K, s, dm, qt, kt, dm->n_k, 0, dm->F, st);
+  if (launch_pool(Q, K, s, dm, qt, kt, dm->n_k, 0, dm->F, st) != hipSuccess) return LF_ERR_HIP;
   const bool retrieve = b->k_frames < dm->m;
-  if (retrieve)
-    hipLaunchKernelGGL(lf_frame_mean_kernel, dim3((unsigned)(dm->H * dm->m)), dim3(dm->d), 0, st,
-                       kt, kh, dm->d, dm->nb, dm->n_k, dm->m, b->n_sink, 0, dm->m);
-  launch_select(b, dm, qt, kt, kh, dm->n_k, dm->m > 0 ? dm->m : 1, 0, indices, st);
-  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+  if (retrieve &&
+      lf_launch(lf_frame_mean_kernel, dim3((unsigned)(dm->H * dm->m)), dim3(dm->d), 0, st,
+                (const float*)kt, kh, dm->d, dm->nb, dm->n_k, dm->m, b->n_sink, 0, dm->m) != hipSuccess)
+    return LF_ERR_HIP;
+  return launch_select(b, dm, qt, kt, kh, dm->n_k, dm->m > 0 ? dm->m : 1, 0, indices, st) == hipSuccess
+             ? LF_OK : LF_ERR_HIP;
 }
 
 // Pooled-key cache: kt for max_frames * nb blocks, then kh for max_frames frames (all frames,
@@ -454,11 +456,11 @@ int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm,
   hipStream_t st = (hipStream_t)stream;
   float* kt = (float*)kcache;
   float* kh = kt + (size_t)dm->H * max_frames * dm->nb * dm->d;
-  launch_pool(nullptr, K, s, dm, nullptr, kt, max_frames * dm->nb, frame0, frame1, st);
-  hipLaunchKernelGGL(lf_frame_mean_kernel, dim3((unsigned)(dm->H * (frame1 - frame0))), dim3(dm->d), 0, st,
-                     kt, kh, dm->d, dm->nb, max_frames * dm->nb, max_frames, frame0, frame0,
-                     frame1 - frame0);
-  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+  if (launch_pool(nullptr, K, s, dm, nullptr, kt, max_frames * dm->nb, frame0, frame1, st) != hipSuccess)
+    return LF_ERR_HIP;
+  return lf_launch(lf_frame_mean_kernel, dim3((unsigned)(dm->H * (frame1 - frame0))), dim3(dm->d), 0, st,
+                   (const float*)kt, kh, dm->d, dm->nb, max_frames * dm->nb, max_frames, frame0, frame0,
+                   frame1 - frame0) == hipSuccess ? LF_OK : LF_ERR_HIP;
 }
 
 int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
@@ -470,10 +472,9 @@ int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int m
   const float* kh = kt + (size_t)dm->H * max_frames * dm->nb * dm->d;
   // one launch pools Q and, when the keys are given, the block means of the current chunk
   // (its frame means are not needed while it is current: the candidate frames are history)
-  if (Kcur)
-    launch_pool(Q, Kcur, s, dm, qt, kt, max_frames * dm->nb, dm->F_h, dm->F, st);
-  else
-    launch_pool(Q, nullptr, s, dm, qt, nullptr, 1, 0, 0, st);
-  launch_select(b, dm, qt, kt, kh, max_frames * dm->nb, max_frames, b->n_sink, indices, st);
-  return hipGetLastError() == hipSuccess ? LF_OK : LF_ERR_HIP;
+  const hipError_t rc = Kcur ? launch_pool(Q, Kcur, s, dm, qt, kt, max_frames * dm->nb, dm->F_h, dm->F, st)
+                             : launch_pool(Q, nullptr, s, dm, qt, nullptr, 1, 0, 0, st);
+  if (rc != hipSuccess) return LF_ERR_HIP;
+  return launch_select(b, dm, qt, kt, kh, max_frames * dm->nb, max_frames, b->n_sink, indices, st) == hipSuccess
+             ? LF_OK : LF_ERR_HIP;
 }

@@ -72,9 +72,45 @@ def test_chunk_budget_matches_oracle(lib):
             for name in ("n_hist_frames", "frames_per_chunk", "n_sink", "n_win", "k_frames",
                          "k_blocks", "current_mandatory", "list_len"):
                 assert getattr(got, name) == getattr(want, name), (sch, i, name)
-            assert got.keep_ratio == want.keep_ratio, (sch, i)   # bit-identical binary64
+            # the two sides evaluate Eq. 5-6 with differently arranged sums
+            assert abs(got.keep_ratio - want.keep_ratio) <= 1e-14, (sch, i)
             count += 1
     assert count > 3000
+
+
+def _golden(name):
+    with open(os.path.join(ROOT, "tests", "golden", name)) as fh:
+        return [ln.split() for ln in fh if ln.strip() and not ln.startswith("#")]
+
+
+def test_chunk_budget_matches_hand_computed_counts(lib):
+    """The C call against the golden tables (hand arithmetic from the benchmark wording and
+    from Eq. 5-6 with the appendix table), not against the oracle."""
+    for name, chunk, k_blocks, list_len in _golden("baseline_configs.txt"):
+        chunk = int(chunk)
+        w = {"first_chunk": synth.cfg_first_chunk, "mid_rollout": synth.cfg_mid_rollout,
+             "last_chunk": synth.cfg_last_chunk}.get(name, lambda: synth.cfg_rollout(chunk, 0))()
+        b = lf.lf_chunk_budget(chunk, w.schedule)
+        assert (b.k_blocks, b.list_len) == (int(k_blocks), int(list_len)), (name, chunk)
+    for setting, chunk, k_blocks in _golden("cag_list_len.txt"):
+        w = (synth.cfg_paper_5s if setting == "5s" else synth.cfg_paper_15s)(int(chunk))
+        b = lf.lf_chunk_budget(int(chunk), w.schedule)
+        assert (b.k_blocks, b.list_len, b.current_mandatory) == (int(k_blocks), int(k_blocks), 0)
+
+
+def test_chunk_budget_rejects_a_schedule_that_leaves_the_unit_interval(lib):
+    """s_base 0.5 / s_target 0.1 over 7 chunks: s_2 = -0.112 (not a ratio), s_7 = 0.173."""
+    sch = lf.make_schedule(synth.Schedule(mode=synth.SCHED_CAG, n_chunks=7, frame_len=1536,
+                                          ratio_of=synth.OF_ALL, current_mandatory=0,
+                                          first_chunk_dense=1, s_base=0.5, s_target=0.1))
+    out = lf.lf_budget()
+    assert lib.lf_chunk_budget(2, C.byref(sch), C.byref(out)) == -8
+    assert lib.lf_chunk_budget(3, C.byref(sch), C.byref(out)) == 0   # s_3 = 0.0003
+    assert lib.lf_chunk_budget(7, C.byref(sch), C.byref(out)) == 0 and out.k_blocks == 216
+    with pytest.raises(ValueError):
+        O.chunk_budget(2, synth.Schedule(mode=synth.SCHED_CAG, n_chunks=7, frame_len=1536,
+                                         ratio_of=synth.OF_ALL, current_mandatory=0,
+                                         first_chunk_dense=1, s_base=0.5, s_target=0.1))
 
 
 def test_chunk_budget_errors(lib):
