@@ -247,6 +247,31 @@ int lf_select_mask_cached(const void* Q, const void* Kcache, void* kcache, size_
                           int32_t* indices, void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 
+/*
+ * Mask selection for callers that cannot allocate or hand over scratch memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same
+ * kernels and same lists as lf_select_mask, but the intermediates (q_tilde, k_tilde, k_hat) live
+ * in a device array that is part of the library itself: lf_static_scratch_bytes() = 16 MiB per
+ * GPU, held from the moment the library is loaded on that GPU until the process ends.  The call
+ * allocates and frees nothing.
+ *   lf_init                   looks up the array's address on the CURRENT device (once per
+ *                             device; later calls return at once).  lf_select_mask_static does
+ *                             this itself on its first call per device; call lf_init beforehand
+ *                             where that lookup must not happen inside the call (e.g. before
+ *                             starting a graph capture).  Returns LF_OK or LF_ERR_HIP.
+ *   lf_select_mask_static     arguments as lf_select_mask, without the workspace.
+ * Limits and sharing: shapes whose lf_workspace_bytes() exceeds lf_static_scratch_bytes() are
+ * rejected with LF_ERR_WORKSPACE (the last-chunk configuration at 12 heads needs 3.7 MiB, at 40
+ * heads 12.3 MiB).  All calls on one GPU share that GPU's array: calls that may overlap on the
+ * same GPU (different streams) race; calls on one stream are ordered and safe.  Nothing has to
+ * be cleared between calls: every intermediate a call reads it has written first.
+ * Errors: as lf_select_mask, with LF_ERR_WORKSPACE as above.
+ */
+int lf_init(void);
+size_t lf_static_scratch_bytes(void);
+int lf_select_mask_static(const void* Q, const void* Kcache, const lf_shape* shape,
+                          const lf_budget* budget, int32_t* indices, void* hip_stream);
+
 /* Static, NUL-terminated description of an lf_status value. */
 const char* lf_strerror(int status);
 

@@ -14,6 +14,9 @@
                                  // dynamic LDS below 64 KiB, so the size is known to fit
                                  // before anything is enqueued
 
+// Size of the library-owned device scratch behind lf_select_mask_static (per GPU).
+#define LF_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+
 // Derived sizes of one call; filled by lf_derive() after validation.
 struct lf_dims {
   int H, d, n, f, F, F_h, nb, n_q, n_k, m;
@@ -33,6 +36,9 @@ int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm,
 int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
                             const lf_shape* s, const lf_budget* b, const lf_dims* dm, int32_t* indices,
                             void* workspace, void* stream);
+// Device address of the library's static scratch on the current device (looked up on the first
+// call per device); LF_OK or LF_ERR_HIP.
+int lf_static_scratch(void** ptr);
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
                    const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
                    void* O, void* stream);

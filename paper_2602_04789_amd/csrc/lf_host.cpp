@@ -221,6 +221,27 @@ extern "C" int lf_select_mask(const void* Q, const void* K, const lf_shape* s, c
   return lf_launch_select(Q, K, s, b, &dm, indices, workspace, stream);
 }
 
+extern "C" int lf_init(void) {
+  void* p;
+  return lf_static_scratch(&p);
+}
+
+extern "C" size_t lf_static_scratch_bytes(void) { return LF_STATIC_SCRATCH_BYTES; }
+
+extern "C" int lf_select_mask_static(const void* Q, const void* K, const lf_shape* s,
+                                     const lf_budget* b, int32_t* indices, void* stream) {
+  if (!Q || !K || !s || !b || !indices) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, b, &dm);
+  if (rc != LF_OK) return rc;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(indices, 4)) return LF_ERR_ALIGN;
+  if (dm.ws_bytes > LF_STATIC_SCRATCH_BYTES) return LF_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = lf_static_scratch(&ws);
+  if (rc != LF_OK) return rc;
+  return lf_launch_select(Q, K, s, b, &dm, indices, ws, stream);
+}
+
 // Bytes of the pooled-key cache; 0 when the sizes are unusable.
 static size_t kcache_bytes(const lf_dims& dm, int32_t max_frames) {
   if (max_frames < 1 || max_frames > LF_MAX_HIST_FRAMES + 64) return 0;

@@ -478,3 +478,27 @@ int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int m
   return launch_select(b, dm, qt, kt, kh, max_frames * dm->nb, max_frames, b->n_sink, indices, st) == hipSuccess
              ? LF_OK : LF_ERR_HIP;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Scratch owned by the library, for callers that cannot allocate: one file-scope device array
+// per GPU (every device the library's code object is loaded on holds its own copy, at its own
+// address, until the process ends).  The array's name is a host-side handle, not a device
+// address: its address is looked up once per device and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[LF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // zero-initialised; written once per device (same value if raced)
+}
+
+int lf_static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LF_ERR_HIP;
+  void* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LF_ERR_HIP;
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+  }
+  *out = p;
+  return LF_OK;
+}

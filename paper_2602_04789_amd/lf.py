@@ -92,6 +92,12 @@ def load() -> C.CDLL:
     lib.lf_select_mask_cached.argtypes = [vp, vp, vp, C.c_size_t, C.c_int32, C.POINTER(lf_shape),
                                           C.POINTER(lf_budget), vp, vp, C.c_size_t, vp]
     lib.lf_select_mask_cached.restype = C.c_int
+    lib.lf_init.argtypes = []
+    lib.lf_init.restype = C.c_int
+    lib.lf_static_scratch_bytes.argtypes = []
+    lib.lf_static_scratch_bytes.restype = C.c_size_t
+    lib.lf_select_mask_static.argtypes = [vp, vp, C.POINTER(lf_shape), C.POINTER(lf_budget), vp, vp]
+    lib.lf_select_mask_static.restype = C.c_int
     lib.lf_strerror.argtypes = [C.c_int]
     lib.lf_strerror.restype = C.c_char_p
     lib.lf_version.argtypes = []
@@ -190,6 +196,30 @@ def lf_select_mask(Q, Kcache, frame_len: int, block: int, budget: lf_budget, ind
                             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if rc != LF_OK:
         raise LfError(rc, "lf_select_mask")
+    return indices
+
+
+def lf_init() -> None:
+    rc = load().lf_init()
+    if rc != LF_OK:
+        raise LfError(rc, "lf_init")
+
+
+def lf_static_scratch_bytes() -> int:
+    return int(load().lf_static_scratch_bytes())
+
+
+def lf_select_mask_static(Q, Kcache, frame_len: int, block: int, budget: lf_budget, indices,
+                          stream=None):
+    """Mask selection on the library's own static scratch; ``indices`` (int32
+    [H, n_q, list_len], device) is the caller's and is returned.  Allocates nothing."""
+    _check_tensor(Q, "Q")
+    _check_tensor(Kcache, "Kcache")
+    sh = make_shape(Q, Kcache, frame_len=frame_len, block=block)
+    rc = load().lf_select_mask_static(Q.data_ptr(), Kcache.data_ptr(), C.byref(sh), C.byref(budget),
+                                      indices.data_ptr(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_select_mask_static")
     return indices
 
 
