@@ -209,6 +209,30 @@ int lf_sparse_attn(const void* Q, const void* Kcache, const void* Vcache,
                    float softmax_scale, void* O, void* hip_stream);
 
 /*
+ * Blockwise sparse attention (Eq. 13) in two phases, for lists written by lf_select_mask with
+ * budget->current_mandatory = 1.  The always-selected current-chunk frames of Eq. 9 put the same
+ * f*nb KV blocks, one contiguous token range, into every list of a head; that part of every row's
+ * softmax is a plain dense attention problem and is computed by a dense kernel (128 query rows
+ * per workgroup share each K/V tile), which leaves an online-softmax state per query row
+ * (reference m, row sum l, unnormalised O, float32) in `workspace`; the list-driven kernel then
+ * continues that state over the first budget->k_blocks entries of each list and writes O.  The
+ * result is the softmax over the union, as lf_sparse_attn computes it in one pass.
+ * Arguments as lf_sparse_attn, plus
+ *   budget     the budget the lists were selected with.  Entries [k_blocks, list_len) of every
+ *              list are taken to be the current chunk's blocks F_h*nb .. n_k-1 (what
+ *              lf_select_mask writes) and are not read.  With current_mandatory = 0 nothing is
+ *              common to all lists and the call is lf_sparse_attn (workspace unused).
+ *   workspace  device scratch of >= lf_attn_workspace_bytes(shape), 256-byte aligned; contents
+ *              need not be preserved or cleared between calls.
+ * Errors: as lf_sparse_attn and LF_ERR_BUDGET as lf_select_mask; LF_ERR_WORKSPACE.
+ */
+size_t lf_attn_workspace_bytes(const lf_shape* shape);
+int lf_sparse_attn_split(const void* Q, const void* Kcache, const void* Vcache,
+                         const lf_shape* shape, const lf_budget* budget, const int32_t* indices,
+                         float softmax_scale, void* O, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
  * Pooled-key cache (an extension the paper does not describe; it follows from its setting).
  * The keys of a finished chunk never change again (Sec. 3: the rollout appends each generated
  * chunk's K/V to the cache and later chunks only read it), so their block means and frame means

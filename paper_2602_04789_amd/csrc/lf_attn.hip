@@ -20,6 +20,15 @@
 // reference: P = exp2(s*c - m) with a per-row m that is moved (and O, l rescaled) only when a
 // row sum shows that it has fallen too far behind the scores; the common path takes no row
 // maximum.  The result is the same softmax: the reference cancels in O / l.
+//
+// The same per-wavefront step serves two kernels.  The list-driven one above, and a dense one
+// for KV blocks that every query block of a head keeps (the always-selected current-chunk
+// frames of Eq. 9): there a workgroup of 4 wavefronts owns 128 consecutive query rows and
+// walks one contiguous KV token range, so a K/V half tile brought into LDS serves 4 x 32 query
+// rows instead of 2 x 32 (8 wavefronts per workgroup measured slower: then the two wavefronts
+// of a SIMD wait at the same barrier and run their phases in step).  The dense kernel leaves its online-softmax state (reference m, row
+// sum l, unnormalised O) per query row in float32, and the list-driven kernel can start from
+// such a state instead of from zero: together they compute one softmax over the union.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -34,8 +43,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int int32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 128;
-constexpr int kMaxEnt = 512;  // list entries decoded per pass (power of two)
+constexpr int kMaxEnt = 512;  // half tiles decoded per pass (power of two)
 
 struct AttnArgs {
   const uint16_t* Q;
@@ -45,9 +53,18 @@ struct AttnArgs {
   const int32_t* idx;
   int64_t q_stride_tok, q_stride_head, k_stride_tok, k_stride_head;
   int64_t v_stride_tok, v_stride_head, o_stride_tok, o_stride_head;
-  int n, nb, n_q, n_k, list_len;
+  int n, nb, n_q, n_k;
+  int list_len;     // entries walked per list
+  int list_stride;  // entries between two lists in memory
   int total_wg, wg_per_xcd;
   float c;  // softmax_scale * log2(e)
+  // Online-softmax state per query row, float32: O unnormalised [H][q_len][d] and (m, l)
+  // [H][q_len].  The dense kernel writes it; the list-driven kernel starts from it when
+  // state_o is not null.
+  float* state_o;
+  float2* state_ml;
+  // dense kernel only: query rows per workgroup, workgroups per head, KV token range
+  int q_len, rows_per_wg, wg_per_head, kv0, kv1;
 };
 
 union Frag {
@@ -80,43 +97,52 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
+// WAVES wavefronts of 32 query rows each per workgroup.  DENSE: the workgroup walks the KV
+// token range [kv0, kv1) and stores its state; otherwise it walks the list of its query block.
+template <int D, int WAVES, bool DENSE>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs a) {
+  constexpr int kThreads = 64 * WAVES;
   constexpr int CH = D / 8;                 // 16-byte chunks per token row
   constexpr int KS = D / 16;                // k-steps of S^T = K Q^T
   constexpr int MB = D / 32;                // 32-row blocks of O^T
   constexpr int RPI = 64 / CH;              // tile rows one wavefront load instruction covers
-  constexpr int LPW = 32 / (RPI * 2);       // load instructions per wavefront, per tile, per tensor
+  constexpr int LPW = 32 / (RPI * WAVES);   // load instructions per wavefront, per tile, per tensor
   constexpr int TILE = 32 * CH;             // uint4 per half tile (32 KV rows)
+  static_assert(LPW >= 1 && LPW * RPI * WAVES == 32, "a half tile must split evenly over the wavefronts");
 
   __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles
   __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
-  __shared__ int2 ent[kMaxEnt / 2];         // (first token, token count) per list entry of a pass
+  __shared__ int2 ent[DENSE ? 1 : kMaxEnt / 2];   // (first token, token count) per list entry of a pass
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
   const int w = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
   if (w >= a.total_wg) return;
-  const int h = w / a.n_q, r = w % a.n_q;
+  const int per_head = DENSE ? a.wg_per_head : a.n_q;
+  const int h = w / per_head, r = w % per_head;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
   const int rh = wave;
   const int ln = lane & 31, kg = lane >> 5;
 
-  const int qtok0 = (r / a.nb) * a.n + (r % a.nb) * 64;
-  const int q_cnt = min(64, a.n - (r % a.nb) * 64);
+  // first query token and number of query rows of this workgroup: a query block of <= 64
+  // tokens, or (dense) an even share of the chunk's rows, which need not follow the blocks
+  const int qtok0 = DENSE ? r * a.rows_per_wg : (r / a.nb) * a.n + (r % a.nb) * 64;
+  const int q_cnt = DENSE ? min(a.rows_per_wg, a.q_len - qtok0) : min(64, a.n - (r % a.nb) * 64);
   const int qrow = 32 * rh + ln;
 
   // The list entries of the first pass are requested first, so that they travel together with
   // the Q fragments instead of after them.
-  const int32_t* list = a.idx + ((int64_t)h * a.n_q + r) * a.list_len;
-  constexpr int EPT = kMaxEnt / 2 / kThreads;   // list entries per thread and pass (two half tiles each)
+  const int32_t* list = DENSE ? nullptr : a.idx + ((int64_t)h * a.n_q + r) * a.list_stride;
+  constexpr int EPT = DENSE ? 1 : kMaxEnt / 2 / kThreads;   // list entries per thread and pass (two half tiles each)
   int pre[EPT];
+  if constexpr (!DENSE) {
 #pragma unroll
-  for (int j = 0; j < EPT; ++j) {
-    const int i = tid + j * kThreads;
-    pre[j] = i < a.list_len ? list[i] : -1;
+    for (int j = 0; j < EPT; ++j) {
+      const int i = tid + j * kThreads;
+      pre[j] = i < a.list_len ? list[i] : -1;
+    }
   }
 
   // Q^T fragments (B operand): lane (column q = ln, k-group kg) holds 8 consecutive channels.
@@ -184,11 +210,15 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
                    "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 lds\n\t"
                    "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 lds"
                    :: "s"(lds0), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(rs));
-    else
+    else if constexpr (LPW == 2)
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                    "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
                    "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
                    :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs));
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(lds0), "v"(off[0]), "s"(rs));
   };
   auto k_rsrc = [&](int2 e) { return tile_rsrc(Kh, (uint32_t)k_row_bytes, e); };
   auto v_rsrc = [&](int2 e) { return tile_rsrc(Vh, (uint32_t)v_row_bytes, e); };
@@ -233,33 +263,69 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
   // the row sums and O stay finite far beyond that range, and O / l does not depend on m_run.
   constexpr float kSumMax = 1.0e30f;
   float m_run = -1.0e30f, l_run = 0.0f;
+  // Accumulator i of oacc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of query row qrow; the
+  // stored state uses the same order within a row, so a lane moves float4s.
+  float* state_row = nullptr;
+  if (a.state_o != nullptr && qrow < q_cnt) {
+    const int64_t row = (int64_t)h * a.q_len + qtok0 + qrow;
+    state_row = a.state_o + row * D;
+    if constexpr (!DENSE) {
+      const float2 ml = a.state_ml[row];
+      m_run = ml.x;
+      l_run = kg == 0 ? ml.y : 0.0f;   // the two lanes of a row each carry part of the sum
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 v = *reinterpret_cast<const float4*>(state_row + 32 * mb + 8 * g + 4 * kg);
+          oacc[mb][4 * g + 0] = v.x; oacc[mb][4 * g + 1] = v.y;
+          oacc[mb][4 * g + 2] = v.z; oacc[mb][4 * g + 3] = v.w;
+        }
+    }
+  }
 
   // Lists are decoded kMaxEnt / 2 entries at a time into LDS: block id -> two half tiles
   // (first token, count); an id outside [0, n_k) becomes two empty ones (count 0).
-  for (int l0 = 0; l0 < a.list_len; l0 += kMaxEnt / 2) {
-    const int l1 = min(a.list_len, l0 + kMaxEnt / 2);
+  // The dense kernel has no list: half tile t is KV tokens [kv0 + 32 t, +32) cut at kv1 (empty
+  // beyond it), all in one pass of an even number of steps.
+  auto dense_half = [&](int t) {
+    const int tok = a.kv0 + 32 * t;
+    return make_int2(min(tok, a.kv1), min(max(a.kv1 - tok, 0), 32));
+  };
+  const int n_entries = DENSE ? (a.kv1 - a.kv0 + 63) / 64 : a.list_len;
+  const int pass_len = DENSE ? n_entries : kMaxEnt / 2;
+  for (int l0 = 0; l0 < n_entries; l0 += pass_len) {
+    const int l1 = min(n_entries, l0 + pass_len);
     const int t0 = 2 * l0, t1 = 2 * l1;   // half-tile steps of this pass
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __syncthreads();
+    if constexpr (!DENSE) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __syncthreads();
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      const int i = l0 + tid + e * kThreads;
-      if (i < l1) {
-        const int c = l0 == 0 ? pre[e] : list[i];
-        const bool ok = (unsigned)c < (unsigned)a.n_k;
-        const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
-        const int cnt = ok ? min(64, a.n - j * 64) : 0;
-        ent[i - l0] = make_int2(tau * a.n + j * 64, cnt);
+      for (int e = 0; e < EPT; ++e) {
+        const int i = l0 + tid + e * kThreads;
+        if (i < l1) {
+          const int c = l0 == 0 ? pre[e] : list[i];
+          const bool ok = (unsigned)c < (unsigned)a.n_k;
+          const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+          const int cnt = ok ? min(64, a.n - j * 64) : 0;
+          ent[i - l0] = make_int2(tau * a.n + j * 64, cnt);
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
     // Software pipeline, one step deep (a step, "tile" below, is one half tile of 32 KV rows):
     // iteration t computes S^T of tile t+1 (matrix core)
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
-    const int2 eb0 = entry(l0);
-    int2 eb = entry(min(l0 + 1, l1 - 1));   // list entry whose half tiles are requested next
-    int2 e0 = lower(eb0), e1 = upper(eb0), e2 = lower(eb);
+    int2 eb = make_int2(0, 0);   // list entry whose half tiles are requested next
+    int2 e0, e1, e2;
+    if constexpr (DENSE) {
+      e0 = dense_half(0); e1 = dense_half(1); e2 = dense_half(2);
+    } else {
+      const int2 eb0 = entry(l0);
+      eb = entry(min(l0 + 1, l1 - 1));
+      e0 = lower(eb0); e1 = upper(eb0); e2 = lower(eb);
+    }
     fetch_k(k_rsrc(e0), buf0);
     fetch_v(v_rsrc(e0), buf0);
     fetch_k(k_rsrc(e1), buf1);
@@ -370,7 +436,9 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
       sacc = snext;
       e0 = e1;
       e1 = e2;
-      if (second) {          // step t + 3 opens the next list entry
+      if constexpr (DENSE) {
+        e2 = dense_half(t + 3);
+      } else if (second) {   // step t + 3 opens the next list entry
         eb = entry(min((t + 3) >> 1, l1 - 1));
         e2 = lower(eb);
       } else {
@@ -383,8 +451,22 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
     }
   }
 
-  // Every wavefront owns its 32 query rows completely: normalise and store.
+  // Every wavefront owns its 32 query rows completely.
   l_run += __shfl_xor(l_run, 32);
+  if constexpr (DENSE) {
+    // leave the state for the list-driven kernel to continue from
+    if (state_row != nullptr) {
+      if (kg == 0) a.state_ml[(int64_t)h * a.q_len + qtok0 + qrow] = make_float2(m_run, l_run);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(state_row + 32 * mb + 8 * g + 4 * kg) =
+              make_float4(oacc[mb][4 * g + 0], oacc[mb][4 * g + 1], oacc[mb][4 * g + 2], oacc[mb][4 * g + 3]);
+    }
+    return;
+  }
+  // normalise and store
   const float inv = l_run > 0.0f ? 1.0f / l_run : 0.0f;   // a list without a valid id gives zero rows
   if (qrow < q_cnt) {
     uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
@@ -403,15 +485,12 @@ __global__ __launch_bounds__(kThreads, 4) void lf_attn_kernel(AttnArgs a) {
 
 }  // namespace
 
-int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
-                   const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
-                   void* O, void* stream) {
-  AttnArgs a;
+static AttnArgs attn_args(const void* Q, const void* K, const void* V, const lf_shape* s,
+                          const lf_dims* dm, float scale) {
+  AttnArgs a = {};
   a.Q = (const uint16_t*)Q;
   a.K = (const uint16_t*)K;
   a.V = (const uint16_t*)V;
-  a.O = (uint16_t*)O;
-  a.idx = indices;
   a.q_stride_tok = s->q_stride_tok;
   a.q_stride_head = s->q_stride_head;
   a.k_stride_tok = s->k_stride_tok;
@@ -424,13 +503,53 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
   a.nb = dm->nb;
   a.n_q = dm->n_q;
   a.n_k = dm->n_k;
+  a.q_len = dm->f * dm->n;
+  a.c = scale * 1.4426950408889634f;
+  return a;
+}
+
+// List-driven kernel: walks the first list_len entries of every list (lists are list_stride
+// entries apart); with a state (state_o, state_ml) it continues that online softmax.
+int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
+                   const lf_dims* dm, const int32_t* indices, int32_t list_len, int32_t list_stride,
+                   float scale, void* O, const float* state_o, const float* state_ml, void* stream) {
+  AttnArgs a = attn_args(Q, K, V, s, dm, scale);
+  a.O = (uint16_t*)O;
+  a.idx = indices;
   a.list_len = list_len;
+  a.list_stride = list_stride;
+  a.state_o = const_cast<float*>(state_o);
+  a.state_ml = reinterpret_cast<float2*>(const_cast<float*>(state_ml));
   a.total_wg = dm->H * dm->n_q;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
-  a.c = scale * 1.4426950408889634f;
   const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
   hipStream_t st = (hipStream_t)stream;
-  const hipError_t rc = dm->d == 128 ? lf_launch(lf_attn_kernel<128>, dim3(grid), dim3(kThreads), 0, st, a)
-                                     : lf_launch(lf_attn_kernel<64>, dim3(grid), dim3(kThreads), 0, st, a);
+  const hipError_t rc = dm->d == 128
+      ? lf_launch(lf_attn_kernel<128, 2, false>, dim3(grid), dim3(128), 0, st, a)
+      : lf_launch(lf_attn_kernel<64, 2, false>, dim3(grid), dim3(128), 0, st, a);
+  return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
+}
+
+// Dense kernel over KV tokens [kv0, kv1) for every query row of every head; writes the state.
+// The rows of a head are dealt evenly to ceil(q_len / (32 WAVES)) workgroups.
+int lf_launch_attn_dense(const void* Q, const void* K, const void* V, const lf_shape* s,
+                         const lf_dims* dm, int kv0, int kv1, float scale, float* state_o,
+                         float* state_ml, void* stream) {
+  AttnArgs a = attn_args(Q, K, V, s, dm, scale);
+  a.state_o = state_o;
+  a.state_ml = reinterpret_cast<float2*>(state_ml);
+  a.kv0 = kv0;
+  a.kv1 = kv1;
+  constexpr int kDenseWaves = 4;            // 128 query rows per workgroup, two workgroups per CU
+  const int rows_max = 32 * kDenseWaves;
+  a.wg_per_head = (a.q_len + rows_max - 1) / rows_max;
+  a.rows_per_wg = (a.q_len + a.wg_per_head - 1) / a.wg_per_head;
+  a.total_wg = dm->H * a.wg_per_head;
+  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
+  hipStream_t st = (hipStream_t)stream;
+  const hipError_t rc = dm->d == 128
+      ? lf_launch(lf_attn_kernel<128, kDenseWaves, true>, dim3(grid), dim3(64 * kDenseWaves), 0, st, a)
+      : lf_launch(lf_attn_kernel<64, kDenseWaves, true>, dim3(grid), dim3(64 * kDenseWaves), 0, st, a);
   return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
 }

@@ -40,8 +40,11 @@ int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int m
 // call per device); LF_OK or LF_ERR_HIP.
 int lf_static_scratch(void** ptr);
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
-                   const lf_dims* dm, const int32_t* indices, int32_t list_len, float scale,
-                   void* O, void* stream);
+                   const lf_dims* dm, const int32_t* indices, int32_t list_len, int32_t list_stride,
+                   float scale, void* O, const float* state_o, const float* state_ml, void* stream);
+int lf_launch_attn_dense(const void* Q, const void* K, const void* V, const lf_shape* s,
+                         const lf_dims* dm, int kv0, int kv1, float scale, float* state_o,
+                         float* state_ml, void* stream);
 
 #ifdef __HIPCC__
 #include <hip/hip_runtime.h>

@@ -312,7 +312,48 @@ extern "C" int lf_sparse_attn(const void* Q, const void* K, const void* V, const
       misaligned(indices, 4))
     return LF_ERR_ALIGN;
   float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
-  return lf_launch_attn(Q, K, V, s, &dm, indices, list_len, scale, O, stream);
+  return lf_launch_attn(Q, K, V, s, &dm, indices, list_len, list_len, scale, O, nullptr, nullptr, stream);
+}
+
+// Scratch of lf_sparse_attn_split: O state float32 [H][q_len][d], then (m, l) float32 [H][q_len][2].
+static size_t attn_state_bytes(const lf_dims& dm, size_t* off_ml) {
+  const size_t rows = (size_t)dm.H * dm.f * dm.n;
+  const size_t o = align_up(rows * dm.d * sizeof(float), 256);
+  if (off_ml) *off_ml = o;
+  return o + align_up(rows * 2 * sizeof(float), 256);
+}
+
+extern "C" size_t lf_attn_workspace_bytes(const lf_shape* s) {
+  lf_dims dm;
+  if (lf_derive(s, nullptr, &dm) != LF_OK) return 0;
+  return attn_state_bytes(dm, nullptr);
+}
+
+extern "C" int lf_sparse_attn_split(const void* Q, const void* K, const void* V, const lf_shape* s,
+                                    const lf_budget* b, const int32_t* indices, float softmax_scale,
+                                    void* O, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Q || !K || !V || !s || !b || !indices || !O) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, b, &dm);
+  if (rc != LF_OK) return rc;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return LF_ERR_SHAPE;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
+      misaligned(indices, 4))
+    return LF_ERR_ALIGN;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
+  if (!b->current_mandatory)   // nothing is common to all query blocks: one list-driven pass
+    return lf_launch_attn(Q, K, V, s, &dm, indices, b->list_len, b->list_len, scale, O, nullptr,
+                          nullptr, stream);
+  size_t off_ml = 0;
+  const size_t need = attn_state_bytes(dm, &off_ml);
+  if (!workspace || workspace_bytes < need) return LF_ERR_WORKSPACE;
+  if (misaligned(workspace, 256)) return LF_ERR_ALIGN;
+  float* state_o = (float*)workspace;
+  float* state_ml = (float*)((char*)workspace + off_ml);
+  rc = lf_launch_attn_dense(Q, K, V, s, &dm, dm.F_h * dm.n, dm.F * dm.n, scale, state_o, state_ml, stream);
+  if (rc != LF_OK) return rc;
+  return lf_launch_attn(Q, K, V, s, &dm, indices, b->k_blocks, b->list_len, scale, O, state_o,
+                        state_ml, stream);
 }
 
 extern "C" const char* lf_strerror(int status) {

@@ -84,6 +84,11 @@ def load() -> C.CDLL:
     lib.lf_sparse_attn.argtypes = [vp, vp, vp, C.POINTER(lf_shape), vp, C.c_int32, C.c_float,
                                    vp, vp]
     lib.lf_sparse_attn.restype = C.c_int
+    lib.lf_attn_workspace_bytes.argtypes = [C.POINTER(lf_shape)]
+    lib.lf_attn_workspace_bytes.restype = C.c_size_t
+    lib.lf_sparse_attn_split.argtypes = [vp, vp, vp, C.POINTER(lf_shape), C.POINTER(lf_budget), vp,
+                                         C.c_float, vp, vp, C.c_size_t, vp]
+    lib.lf_sparse_attn_split.restype = C.c_int
     lib.lf_kcache_bytes.argtypes = [C.POINTER(lf_shape), C.c_int32]
     lib.lf_kcache_bytes.restype = C.c_size_t
     lib.lf_kcache_update.argtypes = [vp, C.POINTER(lf_shape), C.c_int32, C.c_int32, C.c_int32, vp,
@@ -292,4 +297,36 @@ def lf_sparse_attn(Q, Kcache, Vcache, indices, frame_len: int, block: int,
                                O.data_ptr(), _stream_ptr(stream))
     if rc != LF_OK:
         raise LfError(rc, "lf_sparse_attn")
+    return O
+
+
+def lf_attn_workspace_bytes(shape: lf_shape) -> int:
+    return int(load().lf_attn_workspace_bytes(C.byref(shape)))
+
+
+def lf_sparse_attn_split(Q, Kcache, Vcache, indices, frame_len: int, block: int, budget: lf_budget,
+                         softmax_scale: float = 0.0, O=None, workspace=None, stream=None):
+    """Blockwise sparse attention in two phases (dense over the current chunk, list-driven over
+    the retrieved blocks); returns O.  ``indices`` as written by lf_select_mask for ``budget``."""
+    import torch
+    _check_tensor(Q, "Q")
+    _check_tensor(Kcache, "Kcache")
+    _check_tensor(Vcache, "Vcache")
+    if not indices.is_cuda or indices.dtype != torch.int32 or not indices.is_contiguous():
+        raise ValueError("indices must be a contiguous int32 GPU tensor [H, n_q, list_len]")
+    if O is None:
+        O = torch.empty_like(Q, memory_format=torch.contiguous_format)
+    _check_tensor(O, "O")
+    sh = make_shape(Q, Kcache, Vcache, O, frame_len=frame_len, block=block)
+    n_q = (sh.q_len // frame_len) * (-(-frame_len // block)) if frame_len > 0 else -1
+    if indices.dim() != 3 or tuple(indices.shape) != (sh.heads, n_q, int(budget.list_len)):
+        raise ValueError("indices must be [H, n_q, budget.list_len]")
+    if workspace is None:
+        workspace = torch.empty(max(lf_attn_workspace_bytes(sh), 256), dtype=torch.uint8, device=Q.device)
+    rc = load().lf_sparse_attn_split(Q.data_ptr(), Kcache.data_ptr(), Vcache.data_ptr(), C.byref(sh),
+                                     C.byref(budget), indices.data_ptr(), float(softmax_scale),
+                                     O.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_sparse_attn_split")
     return O

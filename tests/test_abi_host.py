@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol(lib):
     names = set(re.findall(r"\b(lf_[a-z_]+)\s*\(", text))
     assert {"lf_chunk_budget", "lf_select_mask", "lf_sparse_attn", "lf_workspace_bytes",
             "lf_workspace_layout", "lf_strerror", "lf_version", "lf_kcache_bytes",
-            "lf_kcache_update", "lf_select_mask_cached"} <= names
+            "lf_kcache_update", "lf_select_mask_cached", "lf_sparse_attn_split",
+            "lf_attn_workspace_bytes", "lf_select_mask_static", "lf_init"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert lf.lf_version() >= 100
@@ -216,6 +217,24 @@ def test_sparse_attn_argument_errors_enqueue_nothing(lib):
     _, s2, _ = _good()
     s2.head_dim = 256
     assert call(s=s2) == -2
+
+
+def test_sparse_attn_split_argument_errors_enqueue_nothing(lib):
+    w, sh, b = _good()
+    need = lf.lf_attn_workspace_bytes(sh)
+    assert need >= w.heads * w.q_len * (w.head_dim + 2) * 4
+    call = lambda Q=FAKE, K=FAKE, V=FAKE, s=sh, bb=b, idx=FAKE, sc=0.0, Out=FAKE, ws=FAKE, nbytes=need: \
+        lib.lf_sparse_attn_split(Q, K, V, C.byref(s) if s is not None else None,
+                                 C.byref(bb) if bb is not None else None, idx, sc, Out, ws, nbytes, None)
+    assert call(Q=None) == -1 and call(V=None) == -1 and call(bb=None) == -1 and call(Out=None) == -1
+    assert call(ws=None) == -6 and call(nbytes=need - 1) == -6 and call(ws=FAKE + 16) == -5
+    assert call(sc=-1.0) == -2 and call(K=FAKE + 8) == -5
+    _, _, b2 = _good()
+    b2.list_len -= 1
+    assert call(bb=b2) == -3
+    _, s2, _ = _good()
+    s2.head_dim = 96
+    assert lf.lf_attn_workspace_bytes(s2) == 0 and call(s=s2) == -2
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

@@ -66,9 +66,14 @@ def _run_select(torch, lf, w, x, check_intermediates=True):
     return (Q, K, V), idx, want
 
 
-def _check_attn(torch, lf, w, x, dev, idx, lists, pairs=None):
+def _check_attn(torch, lf, w, x, dev, idx, lists, pairs=None, split=False):
+    """lf_sparse_attn (or, with split, lf_sparse_attn_split) against the oracle's Eq. 13."""
     Q, K, V = dev
-    out = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block)
+    if split:
+        b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+        out = lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b)
+    else:
+        out = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block)
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
@@ -141,6 +146,7 @@ def test_small_cases_match_oracle_everywhere(gpu, name):
     print(f"case {name}: H={w.heads} d={w.head_dim} n={w.frame_len} F={w.frames}", flush=True)
     dev, idx, lists = _run_select(torch, lf, w, x)
     _check_attn(torch, lf, w, x, dev, idx, lists)
+    _check_attn(torch, lf, w, x, dev, idx, lists, split=True)
 
 
 def test_ties_resolve_to_lower_index(gpu):
@@ -437,6 +443,10 @@ def test_full_size_configs(gpu, name):
     print("attention parity (all query blocks)", flush=True)
     got, worst, mean = _check_attn(torch, lf, w, x, dev, idx, lists)
     print(f"{name}: max-abs {worst:.2e} mean-abs {mean:.2e}", flush=True)
+    if w.schedule.current_mandatory and w.hist_frames > 0:
+        print("attention parity, dense + list-driven phases (all query blocks)", flush=True)
+        _, worst2, mean2 = _check_attn(torch, lf, w, x, dev, idx, lists, split=True)
+        print(f"{name} split: max-abs {worst2:.2e} mean-abs {mean2:.2e}", flush=True)
     # size-independent properties on the whole output: finite; |O| bounded by max |V|
     vmax = float(np.abs(_host_f32(x["V"])).max())
     assert np.abs(got).max() <= vmax * 1.01
@@ -459,3 +469,5 @@ def test_rollout_calls_40_heads(gpu, chunk, step):
     pairs = [(h, r) for h in (0, 19, 39) for r in range(n_q)]
     _, worst, mean = _check_attn(torch, lf, w, x, dev, idx, lists, pairs=pairs)
     print(f"rollout chunk {chunk} step {step}: max-abs {worst:.2e} mean-abs {mean:.2e}", flush=True)
+    _, worst, mean = _check_attn(torch, lf, w, x, dev, idx, lists, pairs=pairs, split=True)
+    print(f"rollout chunk {chunk} step {step} split: max-abs {worst:.2e} mean-abs {mean:.2e}", flush=True)
