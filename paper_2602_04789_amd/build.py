@@ -17,6 +17,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblf_hsa.so")
+BENCH_LIB = os.path.join(PKG, "liblf_bench.so")
 OBJ = os.path.join(PKG, "_build")
 
 SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip"]
@@ -66,6 +67,10 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
             print(out)
         objs.append(obj)
     _run([hipcc, "-shared", "-o", LIB] + objs + ["--offload-arch=gfx950"])
+    # the benchmark's micro-benchmarks: a library of their own, not linked into the product
+    bobj = os.path.join(OBJ, "lf_bench_hip.o")
+    _run([hipcc, "-c", os.path.join(CSRC, "lf_bench.hip"), "-o", bobj] + COMMON + DEVICE)
+    _run([hipcc, "-shared", "-o", BENCH_LIB, bobj, "--offload-arch=gfx950"])
     return LIB
 
 

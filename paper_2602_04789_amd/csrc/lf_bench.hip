@@ -1,0 +1,91 @@
+// Two micro-benchmarks that put a measured ceiling next to the published peaks the roofline
+// fractions are taken against.  They are not part of the hot path and live in a library of
+// their own (liblf_bench.so), which only the benchmark script loads.
+//
+//   lfb_stream_read  streams a buffer once with 16-byte loads (what the pooling pass of mask
+//                    selection does with Q and K), nothing else: achievable read bandwidth.
+//   lfb_mfma_loop    back-to-back v_mfma_f32_32x32x16_bf16 on register operands, four
+//                    independent accumulators per wavefront, two wavefronts per SIMD:
+//                    achievable matrix rate at the clock the chip sustains under that load.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kReadThreads = 256;
+constexpr int kInFlight = 8;   // 16-byte loads a thread has outstanding
+
+__global__ __launch_bounds__(kReadThreads) void stream_read_kernel(const uint4* __restrict__ src,
+                                                                   size_t n16, uint32_t* sink) {
+  // a workgroup walks consecutive spans of kInFlight * 256 * 16 bytes, dealt round-robin
+  const size_t span = (size_t)kInFlight * kReadThreads;
+  uint32_t acc = 0;
+  for (size_t base = (size_t)blockIdx.x * span; base < n16; base += (size_t)gridDim.x * span) {
+    uint4 v[kInFlight];
+#pragma unroll
+    for (int i = 0; i < kInFlight; ++i) {
+      const size_t j = base + (size_t)i * kReadThreads + threadIdx.x;
+      v[i] = j < n16 ? src[j] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < kInFlight; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+  }
+  if (acc == 0x9e3779b9u) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
+__global__ __launch_bounds__(512, 1) void mfma_loop_kernel(float* sink, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+    b[i] = (__bf16)(float)((threadIdx.x * 7 + i) & 1);
+  }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) c0[i] = c1[i] = c2[i] = c3[i] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+  if (s == -1.0f) sink[0] = s;   // never true (all terms are non-negative)
+}
+
+}  // namespace
+
+extern "C" {
+
+// Reads `bytes` (a multiple of 16) of device memory at `buf` once.  Returns 0 or a hipError_t.
+int lfb_stream_read(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+  if (!buf || !sink || bytes % 16) return (int)hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  const size_t span = (size_t)kInFlight * kReadThreads;
+  size_t grid = (n16 + span - 1) / span;
+  if (grid > 256 * 16) grid = 256 * 16;
+  if (grid == 0) return 0;
+  void* args[] = {(void*)&buf, (void*)&n16, (void*)&sink};
+  return (int)hipLaunchKernel(reinterpret_cast<const void*>(stream_read_kernel), dim3((unsigned)grid),
+                              dim3(kReadThreads), args, 0, (hipStream_t)hip_stream);
+}
+
+// 256 workgroups of 8 wavefronts, each wavefront issuing 16 * iters matrix instructions of
+// 2 * 32 * 32 * 16 FLOP.  *flop (host) receives the FLOP count of the launch.
+int lfb_mfma_loop(int iters, void* sink, double* flop, void* hip_stream) {
+  if (!sink || iters < 1) return (int)hipErrorInvalidValue;
+  if (flop) *flop = 256.0 * 8.0 * 16.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
+  void* args[] = {(void*)&sink, (void*)&iters};
+  return (int)hipLaunchKernel(reinterpret_cast<const void*>(mfma_loop_kernel), dim3(256), dim3(512),
+                              args, 0, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"
