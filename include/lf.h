@@ -296,6 +296,40 @@ size_t lf_static_scratch_bytes(void);
 int lf_select_mask_static(const void* Q, const void* Kcache, const lf_shape* shape,
                           const lf_budget* budget, int32_t* indices, void* hip_stream);
 
+/*
+ * Producer of Q and K beside the hot path ("Efficient Deployment": the paper deploys fused
+ * RoPE and RMSNorm kernels next to the sparse attention; it defines neither, so these are the
+ * textbook operators).  For every token l and head h of a token-major activation X[l][h*d + c]:
+ *   RMSNorm   y_c = x_c / sqrt(mean(x^2) + eps) * g_c, the mean taken over the d channels of the
+ *             head (across_heads = 0) or over all H*d channels of the token (across_heads = 1);
+ *   rotation  channel pair i of the head by the token's angle theta[l][i], given as cos and sin:
+ *             (a, b) -> (a cos - b sin, a sin + b cos); pairing 0: pair i = channels (2i, 2i+1),
+ *             pairing 1: pair i = channels (i, i + d/2).  One table serves all heads;
+ *   output    Y[h][l][c] bfloat16, head-major: with Y pointing into Q or at the first token of
+ *             the current chunk inside the K cache, and y_stride_* equal to that tensor's
+ *             strides, the result is exactly what lf_select_mask and lf_sparse_attn read.
+ * Arithmetic: float32 throughout, one rounding to bfloat16 at the end.
+ * Arguments
+ *   X     device, bfloat16 [tokens][>= H*d], row stride x_stride_tok elements.
+ *   g     device, float32 [H*d] norm weight.   cos, sin  device, float32 [tokens][d/2].
+ *   Y     device, bfloat16, written.  All pointers 16-byte aligned, strides multiples of 8.
+ * Errors: LF_ERR_NULL, LF_ERR_SHAPE (head_dim not 64 or 128, sizes < 1, strides too small,
+ *   flags other than 0 / 1, eps negative or not finite), LF_ERR_ALIGN, LF_ERR_HIP.
+ */
+typedef struct {
+  int32_t heads;        /* H */
+  int32_t head_dim;     /* d: 64 or 128 */
+  int32_t tokens;       /* L */
+  int32_t across_heads; /* 0 / 1 */
+  int32_t pairing;      /* 0 interleaved, 1 half */
+  float eps;
+  int64_t x_stride_tok; /* elements, >= H*d */
+  int64_t y_stride_tok, y_stride_head;
+} lf_producer_shape;
+
+int lf_qk_norm_rope(const void* X, const float* g, const float* cos_table, const float* sin_table,
+                    const lf_producer_shape* shape, void* Y, void* hip_stream);
+
 /* Static, NUL-terminated description of an lf_status value. */
 const char* lf_strerror(int status);
 

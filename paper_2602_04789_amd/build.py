@@ -20,7 +20,7 @@ LIB = os.path.join(PKG, "liblf_hsa.so")
 BENCH_LIB = os.path.join(PKG, "liblf_bench.so")
 OBJ = os.path.join(PKG, "_build")
 
-SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip"]
+SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip", "lf_producer.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

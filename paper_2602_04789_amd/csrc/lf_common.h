@@ -36,6 +36,8 @@ int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm,
 int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
                             const lf_shape* s, const lf_budget* b, const lf_dims* dm, int32_t* indices,
                             void* workspace, void* stream);
+int lf_launch_qk_norm_rope(const void* X, const float* g, const float* cosv, const float* sinv,
+                           const lf_producer_shape* p, void* Y, void* stream);
 // Device address of the library's static scratch on the current device (looked up on the first
 // call per device); LF_OK or LF_ERR_HIP.
 int lf_static_scratch(void** ptr);

@@ -356,6 +356,25 @@ extern "C" int lf_sparse_attn_split(const void* Q, const void* K, const void* V,
                         state_ml, stream);
 }
 
+extern "C" int lf_qk_norm_rope(const void* X, const float* g, const float* cos_table,
+                               const float* sin_table, const lf_producer_shape* p, void* Y,
+                               void* stream) {
+  if (!X || !g || !cos_table || !sin_table || !p || !Y) return LF_ERR_NULL;
+  if (p->head_dim != 64 && p->head_dim != 128) return LF_ERR_SHAPE;
+  if (p->heads < 1 || p->tokens < 1 || p->heads > (1 << 16)) return LF_ERR_SHAPE;
+  if ((p->across_heads != 0 && p->across_heads != 1) || (p->pairing != 0 && p->pairing != 1))
+    return LF_ERR_SHAPE;
+  if (!(p->eps >= 0.0f) || isinf(p->eps)) return LF_ERR_SHAPE;
+  if (p->x_stride_tok < (int64_t)p->heads * p->head_dim || p->y_stride_tok < p->head_dim ||
+      p->y_stride_head < 0)
+    return LF_ERR_SHAPE;
+  if (p->x_stride_tok % 8 || p->y_stride_tok % 8 || p->y_stride_head % 8) return LF_ERR_ALIGN;
+  if (misaligned(X, 16) || misaligned(Y, 16) || misaligned(g, 16) || misaligned(cos_table, 16) ||
+      misaligned(sin_table, 16))
+    return LF_ERR_ALIGN;
+  return lf_launch_qk_norm_rope(X, g, cos_table, sin_table, p, Y, stream);
+}
+
 extern "C" const char* lf_strerror(int status) {
   switch (status) {
     case LF_OK: return "ok";

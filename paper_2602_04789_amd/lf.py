@@ -50,6 +50,12 @@ class lf_shape(C.Structure):
                 ("o_stride_tok", C.c_int64), ("o_stride_head", C.c_int64)]
 
 
+class lf_producer_shape(C.Structure):
+    _fields_ = [("heads", C.c_int32), ("head_dim", C.c_int32), ("tokens", C.c_int32),
+                ("across_heads", C.c_int32), ("pairing", C.c_int32), ("eps", C.c_float),
+                ("x_stride_tok", C.c_int64), ("y_stride_tok", C.c_int64), ("y_stride_head", C.c_int64)]
+
+
 class LfError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -89,6 +95,8 @@ def load() -> C.CDLL:
     lib.lf_sparse_attn_split.argtypes = [vp, vp, vp, C.POINTER(lf_shape), C.POINTER(lf_budget), vp,
                                          C.c_float, vp, vp, C.c_size_t, vp]
     lib.lf_sparse_attn_split.restype = C.c_int
+    lib.lf_qk_norm_rope.argtypes = [vp, vp, vp, vp, C.POINTER(lf_producer_shape), vp, vp]
+    lib.lf_qk_norm_rope.restype = C.c_int
     lib.lf_kcache_bytes.argtypes = [C.POINTER(lf_shape), C.c_int32]
     lib.lf_kcache_bytes.restype = C.c_size_t
     lib.lf_kcache_update.argtypes = [vp, C.POINTER(lf_shape), C.c_int32, C.c_int32, C.c_int32, vp,
@@ -330,3 +338,29 @@ def lf_sparse_attn_split(Q, Kcache, Vcache, indices, frame_len: int, block: int,
     if rc != LF_OK:
         raise LfError(rc, "lf_sparse_attn_split")
     return O
+
+
+def lf_qk_norm_rope(X, g, cos_table, sin_table, heads: int, Y, eps: float = 1e-6,
+                    across_heads: bool = False, pairing: int = 0, stream=None):
+    """RMSNorm + rotary embedding of the token-major activation X [L, >= H*d] (bfloat16) into the
+    head-major tensor Y [H, L, d] (bfloat16; may be a view into Q or into the K cache)."""
+    import torch
+    if X.dtype != torch.bfloat16 or Y.dtype != torch.bfloat16 or X.dim() != 2 or Y.dim() != 3:
+        raise ValueError("X must be bfloat16 [L, H*d] and Y bfloat16 [H, L, d]")
+    if X.stride(1) != 1 or Y.stride(2) != 1 or not (X.is_cuda and Y.is_cuda):
+        raise ValueError("X and Y must be GPU tensors with contiguous channels")
+    for t in (g, cos_table, sin_table):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("g, cos_table, sin_table must be contiguous float32 GPU tensors")
+    p = lf_producer_shape()
+    p.heads, p.head_dim, p.tokens = int(heads), int(Y.shape[2]), int(X.shape[0])
+    p.across_heads, p.pairing, p.eps = int(bool(across_heads)), int(pairing), float(eps)
+    p.x_stride_tok, p.y_stride_tok, p.y_stride_head = int(X.stride(0)), int(Y.stride(1)), int(Y.stride(0))
+    if tuple(Y.shape[:2]) != (p.heads, p.tokens) or g.numel() != p.heads * p.head_dim \
+            or tuple(cos_table.shape) != (p.tokens, p.head_dim // 2) or cos_table.shape != sin_table.shape:
+        raise ValueError("shapes of Y, g or the angle tables do not fit X")
+    rc = load().lf_qk_norm_rope(X.data_ptr(), g.data_ptr(), cos_table.data_ptr(), sin_table.data_ptr(),
+                                C.byref(p), Y.data_ptr(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_qk_norm_rope")
+    return Y

@@ -287,3 +287,37 @@ def small_ragged(seed: int = 11, heads: int = 3, head_dim: int = 128, frame_len:
     return Workload(f"ragged_{frame_len}_{chunk_idx}", heads, head_dim, frame_len,
                     frames_per_chunk, chunk_idx, s, seed=seed, decay=True, sink=True,
                     q_follow=True)
+
+
+# ---------------------------------------------------------------------------
+# Inputs of the Q/K producer (RMSNorm + rotary embedding)
+# ---------------------------------------------------------------------------
+
+def make_producer_inputs(tokens: int, heads: int, head_dim: int, seed: int,
+                         grid_hw: Tuple[int, int] = (30, 52), x_pad: int = 0) -> Dict[str, np.ndarray]:
+    """Token-major activations X [tokens, heads*head_dim + x_pad] (bfloat16 bits; what a
+    projection layer leaves, with a per-channel gain so channels differ in scale), an RMSNorm
+    weight g (float32, around 1) and a rotary angle table theta [tokens, head_dim/2] for video
+    tokens laid out frame by frame on a grid of grid_hw patches: the channel pairs are split into
+    three sections that rotate with the token's frame index, row and column, each section with
+    geometrically spaced frequencies (a generic three-axis rotary construction; the values only
+    have to be plausible angles)."""
+    rng = np.random.default_rng([seed, 77, tokens, heads, head_dim])
+    n = heads * head_dim
+    gain = np.exp(0.5 * rng.standard_normal(n)).astype(np.float32)
+    x = rng.standard_normal((tokens, n), dtype=np.float32) * gain[None, :]
+    X = np.zeros((tokens, n + x_pad), dtype=np.uint16)
+    X[:, :n] = _round_bf16(x)
+    g = (1.0 + 0.1 * rng.standard_normal(n)).astype(np.float32)
+    half = head_dim // 2
+    sec = [half - 2 * (half // 3), half // 3, half // 3]
+    gh, gw = grid_hw
+    l = np.arange(tokens)
+    pos = [l // (gh * gw), (l // gw) % gh, l % gw]
+    cols = []
+    for size, p in zip(sec, pos):
+        freq = 10000.0 ** (-np.arange(size, dtype=np.float64) / max(size, 1))
+        cols.append(p[:, None].astype(np.float64) * freq[None, :])
+    theta = np.concatenate(cols, axis=1)
+    return {"X": X, "g": g, "cos": np.cos(theta).astype(np.float32),
+            "sin": np.sin(theta).astype(np.float32)}

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol(lib):
     assert {"lf_chunk_budget", "lf_select_mask", "lf_sparse_attn", "lf_workspace_bytes",
             "lf_workspace_layout", "lf_strerror", "lf_version", "lf_kcache_bytes",
             "lf_kcache_update", "lf_select_mask_cached", "lf_sparse_attn_split",
-            "lf_attn_workspace_bytes", "lf_select_mask_static", "lf_init"} <= names
+            "lf_attn_workspace_bytes", "lf_select_mask_static", "lf_init", "lf_qk_norm_rope"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert lf.lf_version() >= 100
@@ -235,6 +235,25 @@ def test_sparse_attn_split_argument_errors_enqueue_nothing(lib):
     _, s2, _ = _good()
     s2.head_dim = 96
     assert lf.lf_attn_workspace_bytes(s2) == 0 and call(s=s2) == -2
+
+
+def test_qk_norm_rope_argument_errors_enqueue_nothing(lib):
+    def shape(**kw):
+        p = lf.lf_producer_shape()
+        p.heads, p.head_dim, p.tokens, p.across_heads, p.pairing, p.eps = 12, 128, 4680, 0, 0, 1e-6
+        p.x_stride_tok, p.y_stride_tok, p.y_stride_head = 1536, 128, 128 * 4680
+        for k, v in kw.items():
+            setattr(p, k, v)
+        return p
+    call = lambda X=FAKE, g=FAKE, c=FAKE, s=FAKE, p=None, Y=FAKE: lib.lf_qk_norm_rope(
+        X, g, c, s, C.byref(p if p is not None else shape()), Y, None)
+    assert lib.lf_qk_norm_rope(FAKE, FAKE, FAKE, FAKE, None, FAKE, None) == -1
+    assert call(X=None) == -1 and call(g=None) == -1 and call(c=None) == -1 and call(Y=None) == -1
+    for kw in (dict(head_dim=96), dict(heads=0), dict(tokens=0), dict(across_heads=2), dict(pairing=-1),
+               dict(eps=-1.0), dict(eps=float("inf")), dict(x_stride_tok=1528), dict(y_stride_tok=64)):
+        assert call(p=shape(**kw)) == -2, kw
+    assert call(p=shape(x_stride_tok=1540)) == -5 and call(p=shape(y_stride_head=12)) == -5
+    assert call(X=FAKE + 2) == -5 and call(c=FAKE + 4) == -5
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
