@@ -14,8 +14,12 @@ roofline     dominant kernel (block-sparse attention, bf16 MFMA): the same FLOPs
              kernel's own duration, HIP events on the launch stream inside the timed region.
 select       mask selection as an HBM-bound stage: one read of Q and K (bf16) per call.
 cpu_baseline the numpy oracle on the host cores, on a bounded sample of the same workload.
-measured     what this GPU reaches on a library bf16 GEMM and on a streaming copy (context for
-             the published peaks the roofline fractions are taken against).
+measured     what this GPU reaches on two micro-benchmarks of this repository (a streaming
+             16-byte read and a register-only MFMA loop): ceilings measured in the same run,
+             beside the published peaks the roofline fractions are taken against.
+per_config   the same select / attention figures for the other benchmark configurations and
+             the paper's own operating points, each with its index lists checked against the
+             oracle (--no-per-config skips them).
 """
 from __future__ import annotations
 
@@ -33,14 +37,22 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
-# HBM traffic per launch in bytes, measured offline with rocprofv3 --pmc (FETCH_SIZE then
-# WRITE_SIZE, KiB per dispatch; FETCH_SIZE scaled by 1.994, the factor a plain 256 MiB copy in
-# the same run shows, WRITE_SIZE by 1.000): profiles/last_chunk_pmc_counters.txt.
-# None for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("last_chunk", "attn"): (266600 * 1.994 + 14040) * 1024,
-    ("last_chunk", "select"): ((56190 + 1454 + 8668) * 1.994 + (6752 + 180 + 675)) * 1024,
-}
+PROFILE_COUNTERS = os.path.join(ROOT, "profiles", "last_chunk_pmc_counters.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE / WRITE_SIZE
+    runs, scaled by the copy calibration stated there): the line
+    'traffic_bytes attn=<bytes> select=<bytes> commit=<hash>' of profiles/last_chunk_pmc_counters.txt.
+    Returns ({}, None) when the file or the line is missing."""
+    try:
+        for line in open(PROFILE_COUNTERS):
+            if line.startswith("traffic_bytes "):
+                kv = dict(tok.split("=", 1) for tok in line.split()[1:])
+                return ({"attn": float(kv["attn"]), "select": float(kv["select"])}, kv.get("commit"))
+    except (OSError, KeyError, ValueError):
+        pass
+    return {}, None
 
 
 def _workloads():
@@ -82,7 +94,7 @@ def cpu_baseline(w, x, lists_gpu, out_gpu, budget_s: float = 15.0):
     n_q = lists.shape[1]
     rng = np.random.default_rng(0)
     order = rng.permutation(w.heads * n_q)
-    t_attn, flops, done, worst = 0.0, 0.0, 0, 0.0
+    t_attn, flops, done, worst, err_sum, err_cnt = 0.0, 0.0, 0, 0.0, 0.0, 0
     nb = w.blocks_per_frame
     sizes = np.minimum(w.block, w.frame_len - np.arange(nb) * w.block)
     for flat in order:
@@ -91,7 +103,10 @@ def cpu_baseline(w, x, lists_gpu, out_gpu, budget_s: float = 15.0):
         ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, lists[h, r], w.frame_len, w.block)
         t_attn += time.perf_counter() - t1
         lo, hi = O.block_token_range(r, w.frame_len, w.block)
-        worst = max(worst, float(np.abs(out_gpu[h, lo:hi] - ref).max()))
+        err = np.abs(out_gpu[h, lo:hi] - ref)
+        worst = max(worst, float(err.max()))
+        err_sum += float(err.sum())
+        err_cnt += err.size
         flops += 4.0 * w.head_dim * float(sizes[r % nb]) * float(sizes[lists[h, r] % nb].sum())
         done += 1
         if t_sel + t_attn > budget_s:
@@ -107,38 +122,97 @@ def cpu_baseline(w, x, lists_gpu, out_gpu, budget_s: float = 15.0):
                    f"{w.heads * n_q} (head, query block) pairs ({t_attn:.2f} s), extrapolated "
                    f"to the whole chunk: {est_step_s:.1f} s per step"),
         "lists_match_gpu": lists_match, "sample_max_abs_err_gpu_vs_oracle": worst,
+        "sample_mean_abs_err_gpu_vs_oracle": err_sum / max(err_cnt, 1),
     }
 
 
-def measured_peaks(torch):
-    """Library bf16 GEMM rate and streaming-copy rate on this GPU, for context."""
-    n = 8192
-    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
-    b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
-    for _ in range(3):
-        torch.matmul(a, b)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(10):
-        torch.matmul(a, b)
-    e1.record()
-    torch.cuda.synchronize()
-    gemm = 10 * 2.0 * n ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    del a, b
-    x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    y = torch.empty_like(x)
-    for _ in range(2):
-        y.copy_(x)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(10):
-        y.copy_(x)
-    e1.record()
-    torch.cuda.synchronize()
-    stream = 10 * 2.0 * float(1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9   # read + write
-    del x, y
-    return {"gemm_bf16_8192_tflops": gemm, "stream_copy_1gib_read_plus_write_gbps": stream}
+def measured_peaks(torch, select_bytes: int):
+    """Ceilings measured with this repository's own micro-benchmarks (liblf_bench.so): a streaming
+    16-byte read of as many bytes as mask selection reads, the same over 1 GiB, and a loop of
+    back-to-back bf16 MFMAs on register operands."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2602_04789_amd", "liblf_bench.so")
+    if not os.path.exists(path):
+        return {"error": "liblf_bench.so not built"}
+    lib = C.CDLL(path)
+    lib.lfb_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.lfb_mfma_loop.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, n):
+        for _ in range(3):
+            assert fn() == 0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+
+    out = {}
+    for name, nbytes in (("stream_read_select_bytes_gbps", select_bytes // 16 * 16),
+                         ("stream_read_1gib_gbps", 1 << 30)):
+        buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+        t = timed(lambda: lib.lfb_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), st), 20)
+        out[name] = nbytes / t / 1e9
+        del buf
+    flop = C.c_double()
+    t = timed(lambda: lib.lfb_mfma_loop(4000, sink.data_ptr(), C.byref(flop), st), 5)
+    out["mfma_bf16_loop_tflops"] = flop.value / t / 1e12
+    return out
+
+
+def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
+    """select / attention times of one workload (HIP events on the launch stream), its kept FLOPs,
+    and whether every index list equals the oracle's."""
+    from oracle import hsa_oracle as O
+    x = synth.make_inputs(w)
+    Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
+    sched = lf.make_schedule(w.schedule)
+    b = lf.lf_chunk_budget(w.chunk_idx, sched)
+    sh = lf.make_shape(Q, K, frame_len=w.frame_len, block=w.block)
+    ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+    aws = torch.empty(lf.lf_attn_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.heads, w.frames_per_chunk * w.blocks_per_frame, b.list_len), dtype=torch.int32,
+                      device="cuda")
+    out = torch.empty_like(Q)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        for e in ev:
+            e[0].record()
+            fn()
+            e[1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+
+    sel_ms = timed(lambda: lf.lf_select_mask(Q, K, w.frame_len, w.block, b, indices=idx, workspace=ws))
+    attn_ms = timed(lambda: lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out))
+    lists = idx.cpu().numpy()
+    flops = kept_flops(lists, w)
+    sel_bytes = float((w.q_len + w.kv_len) * w.heads * w.head_dim * 2)
+    res = {"workload": w.name, "heads": w.heads, "q_len": w.q_len, "kv_len": w.kv_len,
+           "list_len": int(b.list_len), "kv_blocks": w.frames * w.blocks_per_frame,
+           "select_ms": sel_ms, "attn_ms": attn_ms, "kept_gflop": flops / 1e9,
+           "attn_tflops": flops / (attn_ms * 1e-3) / 1e12,
+           "attn_frac_of_bf16_peak": flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "select_gbps": sel_bytes / (sel_ms * 1e-3) / 1e9,
+           "select_frac_of_hbm_peak": sel_bytes / (sel_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    if b.current_mandatory:
+        res["attn_split_ms"] = timed(lambda: lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b,
+                                                                     O=out, workspace=aws))
+    if check_lists:
+        ob = O.chunk_budget(w.chunk_idx, w.schedule)
+        want = O.select_mask(synth.bf16_bits_to_f32(x["Q"]), synth.bf16_bits_to_f32(x["K"]),
+                             w.frame_len, w.block, ob)
+        res["lists_match_oracle"] = bool(np.array_equal(want, lists))
+    return res
 
 
 def run_rollout(args, torch, lf, synth):
@@ -213,7 +287,10 @@ def main():
     ap.add_argument("--workload", default="last_chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-measured-peaks", action="store_true",
-                    help="skip the library GEMM / streaming read measurements")
+                    help="skip the micro-benchmarks (streaming read, MFMA loop)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the per_config list (other benchmark configurations, the paper's own "
+                         "operating points, one call per chunk of the 40-head rollout)")
     ap.add_argument("--no-cached-select", action="store_true",
                     help="skip the pooled-key-cache variant of the selection (keeps profiles to the "
                          "four kernels of the main path)")
@@ -296,6 +373,7 @@ def main():
         torch.cuda.synchronize()
         cold = {"select_ms": c[0].elapsed_time(c[1]), "attn_ms": c[1].elapsed_time(c[2])}
         del big
+    traffic, traffic_commit = measured_traffic()
     lists = idx.cpu().numpy()
     flops = kept_flops(lists, w)
     tile_flops = 4.0 * 64 * 64 * w.head_dim * lists.size
@@ -322,11 +400,46 @@ def main():
         "kept_gflop": flops / 1e9, "tile_gflop": tile_flops / 1e9,
         "roofline": {"kernel": "lf_attn_kernel", "bound": "mfma", "achieved": attn_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "attn"))},
+                     "traffic": traffic.get("attn") if args.workload == "last_chunk" else None},
         "select": {"bound": "hbm", "achieved": sel_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                    "frac": sel_gbps / PEAK_HBM_GBPS, "bytes": sel_bytes,
-                   "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "select"))},
+                   "traffic": traffic.get("select") if args.workload == "last_chunk" else None},
+        "traffic_source": {"file": "profiles/last_chunk_pmc_counters.txt", "profile_commit": traffic_commit},
     }
+    # the pooling pass alone (block and frame means of the whole cache, no Q, no scoring): the
+    # HBM-bound part of mask selection on its own bytes
+    kc_all = torch.empty(lf.lf_kcache_bytes(sh, w.frames), dtype=torch.uint8, device="cuda")
+    pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
+    for _ in range(5):
+        lf.lf_kcache_update(K, w.frame_len, w.block, 0, w.frames, w.frames, kc_all)
+    torch.cuda.synchronize()
+    for e in pe:
+        e[0].record()
+        lf.lf_kcache_update(K, w.frame_len, w.block, 0, w.frames, w.frames, kc_all)
+        e[1].record()
+    torch.cuda.synchronize()
+    p_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in pe]))
+    p_bytes = float(w.kv_len * w.heads * w.head_dim * 2)
+    res["pool_only"] = {"what": "lf_kcache_update over the whole cache: pooling kernel + frame means, K only",
+                        "ms": p_ms, "bytes": p_bytes, "achieved": p_bytes / (p_ms * 1e-3) / 1e9, "unit": "GB/s",
+                        "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
+    del kc_all
+    if b.current_mandatory:
+        aws = torch.empty(lf.lf_attn_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
+        se = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
+        for _ in range(5):
+            lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b, O=out, workspace=aws)
+        torch.cuda.synchronize()
+        for e in se:
+            e[0].record()
+            lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b, O=out, workspace=aws)
+            e[1].record()
+        torch.cuda.synchronize()
+        s_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in se]))
+        res["attn_split"] = {"what": "lf_sparse_attn_split: dense kernel over the current chunk + list-driven kernel "
+                                     "over the retrieved blocks", "ms": s_ms,
+                             "achieved": flops / (s_ms * 1e-3) / 1e12, "unit": "TFLOP/s"}
+        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)   # `out` again holds the one-pass result
     if not args.no_cached_select:
         # Selection with the pooled-key cache: the history frames were pooled when their chunk was
         # generated (not timed: it happened in earlier calls of the rollout); a call pools only Q
@@ -374,7 +487,24 @@ def main():
     if cold is not None:
         res["cold_after_1gib_stream"] = cold
     if not args.no_measured_peaks:
-        res["measured"] = measured_peaks(torch)
+        res["measured"] = measured_peaks(torch, int(sel_bytes))
+    if not args.no_per_config:
+        per = []
+        names = [n for n in ("first_chunk", "mid_rollout", "last_chunk", "paper5s_last", "paper15s_late")
+                 if n != args.workload]
+        for n in names:
+            print(f"per_config: {n}", file=sys.stderr, flush=True)
+            per.append(time_config(torch, lf, synth, _workloads()[n](), 20, 5))
+        for chunk in range(1, 8):
+            print(f"per_config: rollout chunk {chunk} (40 heads)", file=sys.stderr, flush=True)
+            per.append(time_config(torch, lf, synth, synth.cfg_rollout(chunk, 0), 10, 3))
+        res["per_config"] = per
+        ro = [p for p in per if p["workload"].startswith("rollout_")]
+        # a 5-second video's 7 chunks x 4 denoising steps, one layer: each chunk's call four times
+        res["rollout_28_calls_est"] = {"ms": 4.0 * sum(p["select_ms"] + p["attn_ms"] for p in ro),
+                                       "kept_gflop": 4.0 * sum(p["kept_gflop"] for p in ro),
+                                       "how": "4 x the sum of the seven 40-head calls above (step 0 of each chunk); "
+                                              "--workload rollout times all 28 calls"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, x, lists, out.float().cpu().numpy().astype(np.float64))
     print(json.dumps(res))

@@ -74,5 +74,23 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
     return LIB
 
 
+def build_sanitized_host(out_dir: str = OBJ) -> str:
+    """Host side of the C ABI alone (lf_host.cpp: validation, budgets, sizes) compiled for the CPU
+    with AddressSanitizer and UndefinedBehaviorSanitizer, linked with the test driver that stands
+    in for the kernel launchers.  Returns the executable's path; no GPU code is involved."""
+    gxx = shutil.which("g++")
+    if not gxx:
+        raise RuntimeError("g++ not found")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "lf_host_sanitized")
+    _run([gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+          "-fno-omit-frame-pointer", "-ffp-contract=off", "-Wall", "-I", os.path.join(ROOT, "include"),
+          "-I", CSRC, os.path.join(CSRC, "lf_host.cpp"),
+          os.path.join(ROOT, "tests", "host_sanitize_driver.cpp"), "-o", exe])
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    if "--sanitize" in sys.argv:
+        print(build_sanitized_host())

@@ -270,7 +270,7 @@ def lf_select_mask_cached(Q, kcache, max_frames: int, kv_len: int, frame_len: in
         indices = torch.empty((sh.heads, n_q, max(int(budget.list_len), 0)), dtype=torch.int32,
                               device=Q.device)
     if workspace is None:
-        workspace = torch.empty(max(sh.heads * n_q * sh.head_dim * 4, 256), dtype=torch.uint8,
+        workspace = torch.empty(max(lf_workspace_bytes(sh, budget), 256), dtype=torch.uint8,
                                 device=Q.device)
     rc = load().lf_select_mask_cached(Q.data_ptr(), None if Kcache is None else Kcache.data_ptr(),
                                       kcache.data_ptr(),

@@ -261,3 +261,17 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(lf, "_LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         lf.lf_chunk_budget(1, synth.cfg_tiny().schedule)
+
+
+def test_host_side_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """lf_host.cpp built for the CPU with -fsanitize=address,undefined and driven through every
+    budget mode and every argument-error path by tests/host_sanitize_driver.cpp."""
+    import subprocess
+    from paper_2602_04789_amd import build
+    exe = build.build_sanitized_host(str(tmp_path))
+    # the environment is passed on as it is; a preloaded library may come before the sanitizer
+    # runtime, which the link-order check would otherwise refuse
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:verify_asan_link_order=0",
+               UBSAN_OPTIONS="print_stacktrace=1")
+    res = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, env=env, timeout=120)
+    assert res.returncode == 0 and "ALL OK" in res.stdout, res.stdout[-3000:]
