@@ -136,7 +136,7 @@ def measured_peaks(torch, select_bytes: int):
         return {"error": "liblf_bench.so not built"}
     lib = C.CDLL(path)
     lib.lfb_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
-    lib.lfb_mfma_loop.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+    lib.lfb_mfma_loop.argtypes = [C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
     sink = torch.zeros(64, dtype=torch.float32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
 
@@ -160,9 +160,63 @@ def measured_peaks(torch, select_bytes: int):
         out[name] = nbytes / t / 1e9
         del buf
     flop = C.c_double()
-    t = timed(lambda: lib.lfb_mfma_loop(4000, sink.data_ptr(), C.byref(flop), st), 5)
-    out["mfma_bf16_loop_tflops"] = flop.value / t / 1e12
+    for name, rnd in (("mfma_bf16_loop_constant_operands_tflops", 0), ("mfma_bf16_loop_random_operands_tflops", 1)):
+        t = timed(lambda: lib.lfb_mfma_loop(4000, rnd, sink.data_ptr(), C.byref(flop), st), 5)
+        out[name] = flop.value / t / 1e12
     return out
+
+
+def run_sensitivity(torch, lf, synth, workload):
+    """How much the attention kernel lengthens when one unit gets more work per step: probe builds
+    of the library (same kernel plus redundant work for one unit, results discarded, output
+    unchanged) are timed against the product build, interleaved, on the same inputs."""
+    from paper_2602_04789_amd import build as B
+    w = _workloads()[workload]()
+    x = synth.make_inputs(w)
+    Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
+    b = lf.lf_chunk_budget(w.chunk_idx, lf.make_schedule(w.schedule))
+    idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    ref = lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block)
+    flops = kept_flops(idx.cpu().numpy(), w)
+    # per step a wavefront does 16 transposing V reads, 8 K fragment reads, 16 MFMAs, 16 exp2
+    cases = [("product", None, "nothing extra"),
+             ("v_reads_x2", "tr", "+16 ds_read_b64_tr_b16 per step (+100 %)"),
+             ("k_reads_x2", "k", "+8 ds_read_b128 per step (+100 %)"),
+             ("mfma_x1.5", "mfma", "+8 v_mfma_f32_32x32x16_bf16 per step (+50 %)"),
+             ("exp_x2", "exp", "+16 v_exp_f32 per step (+100 %)")]
+    handles = []
+    product = lf.load()
+    for name, tag, desc in cases:
+        if tag is None:
+            handles.append(product)
+            continue
+        if not os.path.exists(B.probe_lib(tag)):
+            sys.exit(f"bench.py: {B.probe_lib(tag)} not built")
+        lf._lib, lf._LIB_PATH = None, B.probe_lib(tag)
+        handles.append(lf.load())
+    out = torch.empty_like(Q)
+    res = [{"case": n, "extra": d, "ms": []} for n, _, d in cases]
+    for rep in range(4):
+        for i, h in enumerate(handles):
+            lf._lib = h
+            for _ in range(3):
+                lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(20):
+                lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+            e1.record()
+            torch.cuda.synchronize()
+            res[i]["ms"].append(e0.elapsed_time(e1) / 20)
+            res[i]["output_equals_product"] = bool(torch.equal(out.view(torch.int16), ref.view(torch.int16)))
+    lf._lib = product
+    base = min(res[0]["ms"])
+    for r in res:
+        r["ms_min"] = min(r["ms"])
+        r["slowdown"] = r["ms_min"] / base
+    print(json.dumps({"sensitivity": res, "workload": w.name, "kept_gflop": flops / 1e9,
+                      "baseline_tflops": flops / (base * 1e-3) / 1e12}))
 
 
 def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
@@ -296,6 +350,11 @@ def main():
                          "four kernels of the main path)")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip timing the step as one captured HIP graph")
+    ap.add_argument("--sensitivity", action="store_true",
+                    help="time the probe build of the attention kernel with extra work per unit "
+                         "(prints its own JSON line and exits)")
+    ap.add_argument("--micro-only", action="store_true",
+                    help="run only the micro-benchmarks (streaming read, MFMA loop) and exit")
     ap.add_argument("--cold", action="store_true",
                     help="also time one step right after streaming a 1 GiB buffer through the caches")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -311,6 +370,11 @@ def main():
     lf.load()   # raises if the HIP library is not built: there is no fallback path
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.micro_only:
+        print(json.dumps({"measured": measured_peaks(torch, 115015680)}))
+        return
+    if args.sensitivity:
+        return run_sensitivity(torch, lf, synth, args.workload)
     if args.workload == "rollout":
         if args.steps == 100 and args.warmup == 20:   # the defaults are sized for one chunk
             args.steps, args.warmup = 5, 1

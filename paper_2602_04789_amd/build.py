@@ -18,6 +18,11 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "liblf_hsa.so")
 BENCH_LIB = os.path.join(PKG, "liblf_bench.so")
+PROBES = ("tr", "k", "mfma", "exp")
+
+
+def probe_lib(tag: str) -> str:
+    return os.path.join(PKG, f"liblf_hsa_probe_{tag}.so")
 OBJ = os.path.join(PKG, "_build")
 
 SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip", "lf_producer.hip"]
@@ -67,6 +72,14 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
             print(out)
         objs.append(obj)
     _run([hipcc, "-shared", "-o", LIB] + objs + ["--offload-arch=gfx950"])
+    # probe builds of the library for `bench.py --sensitivity`: the attention kernel with redundant
+    # work per step for one unit each (LF_PROBE_*), everything else the same objects
+    for tag in PROBES:
+        pobj = os.path.join(OBJ, f"lf_attn_probe_{tag}_hip.o")
+        _run([hipcc, "-c", os.path.join(CSRC, "lf_attn.hip"), "-o", pobj, f"-DLF_PROBE_{tag.upper()}"] +
+             COMMON + DEVICE + PER_FILE["lf_attn.hip"])
+        _run([hipcc, "-shared", "-o", probe_lib(tag)] + [o for o in objs if "lf_attn" not in o] + [pobj] +
+             ["--offload-arch=gfx950"])
     # the benchmark's micro-benchmarks: a library of their own, not linked into the product
     bobj = os.path.join(OBJ, "lf_bench_hip.o")
     _run([hipcc, "-c", os.path.join(CSRC, "lf_bench.hip"), "-o", bobj] + COMMON + DEVICE)

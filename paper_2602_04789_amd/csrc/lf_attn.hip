@@ -261,6 +261,13 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   // the reference; +inf if exp2 overflowed, which is also how a row's first score announces
   // itself, m_run starting at -1e30).  bfloat16 and float32 share their exponent range, so P,
   // the row sums and O stay finite far beyond that range, and O / l does not depend on m_run.
+#ifdef LF_PROBE_MFMA
+  f32x16 probe_acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) probe_acc[mb][i] = 0.0f;
+#endif
   constexpr float kSumMax = 1.0e30f;
   float m_run = -1.0e30f, l_run = 0.0f;
   // Accumulator i of oacc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of query row qrow; the
@@ -432,6 +439,41 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
         const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1], oacc[mb], 0, 0, 0);
       }
+      // Probe builds only (liblf_hsa_probe_*.so, for `bench.py --sensitivity`): redundant work added
+      // to every step to see how much the step lengthens when one unit gets more to do.  The extra
+      // results are discarded (the extra products go to an accumulator of their own), the output
+      // is unchanged.
+#ifdef LF_PROBE_TR   // +16 transposing V reads (+100 %)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 0, mb)));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, Vs16 + vaddr(u, 1, mb)));
+          asm volatile("" :: "v"(lo), "v"(hi));
+        }
+#endif
+#ifdef LF_PROBE_K    // +8 K fragment reads (+100 %)
+#pragma unroll
+      for (int s2 = 0; s2 < KS; ++s2) {
+        const uint4 kk = other[kaddr[s2]];
+        asm volatile("" :: "v"(kk.x), "v"(kk.y), "v"(kk.z), "v"(kk.w));
+      }
+#endif
+#ifdef LF_PROBE_MFMA // +8 matrix instructions (+50 %)
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          probe_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0[mb], pf[r2], probe_acc[mb], 0, 0, 0);
+#endif
+#ifdef LF_PROBE_EXP  // +16 exp2 (+100 %)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float ex = __builtin_amdgcn_exp2f(snext[i] * 1.0e-3f);
+        asm volatile("" :: "v"(ex));
+      }
+#endif
       __builtin_amdgcn_s_setprio(3);
       sacc = snext;
       e0 = e1;
@@ -451,6 +493,16 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
     }
   }
 
+#ifdef LF_PROBE_MFMA
+  {
+    float sd = 0.0f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sd += probe_acc[mb][i];
+    if (sd == -123.0f) l_run += 1.0f;   // practically never true: keeps the extra products alive
+  }
+#endif
   // Every wavefront owns its 32 query rows completely.
   l_run += __shfl_xor(l_run, 32);
   if constexpr (DENSE) {

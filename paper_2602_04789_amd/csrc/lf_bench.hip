@@ -6,7 +6,8 @@
 //                    selection does with Q and K), nothing else: achievable read bandwidth.
 //   lfb_mfma_loop    back-to-back v_mfma_f32_32x32x16_bf16 on register operands, four
 //                    independent accumulators per wavefront, two wavefronts per SIMD:
-//                    achievable matrix rate at the clock the chip sustains under that load.
+//                    achievable matrix rate at the clock the chip sustains under that load,
+//                    with constant operands and with pseudo-random ones.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -36,29 +37,52 @@ __global__ __launch_bounds__(kReadThreads) void stream_read_kernel(const uint4* 
   if (acc == 0x9e3779b9u) sink[0] = acc;   // keeps the loads alive; practically never taken
 }
 
+// 32-bit mix (xorshift-multiply) for the pseudo-random operand bits.
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+// RANDOM = false: every operand register holds the same small integers (hardly any bit toggles
+// between consecutive instructions).  RANDOM = true: four different A and four different B
+// operands of pseudo-random bfloat16 values in (-2, 2), cycled through, as activations are: the
+// matrix rate the chip sustains depends on the data, because its clock follows the power drawn.
+template <bool RANDOM>
 __global__ __launch_bounds__(512, 1) void mfma_loop_kernel(float* sink, int iters) {
-  bf16x8 a, b;
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
-    b[i] = (__bf16)(float)((threadIdx.x * 7 + i) & 1);
-  }
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (RANDOM) {
+        const uint32_t ha = mix32((blockIdx.x * 512u + threadIdx.x) * 64u + r * 16u + i);
+        const uint32_t hb = mix32(ha + 0x9e3779b9u);
+        // sign | exponent 0x7c..0x7f (magnitudes 1/8 .. 2) | 7 random mantissa bits
+        const uint16_t ua = (uint16_t)(((ha >> 16) & 0x8000u) | ((0x7cu + (ha & 3u)) << 7) | ((ha >> 8) & 0x7fu));
+        const uint16_t ub = (uint16_t)(((hb >> 16) & 0x8000u) | ((0x7cu + (hb & 3u)) << 7) | ((hb >> 8) & 0x7fu));
+        a[r][i] = __builtin_bit_cast(__bf16, ua);
+        b[r][i] = __builtin_bit_cast(__bf16, ub);
+      } else {
+        a[r][i] = (__bf16)(float)((threadIdx.x + i) & 3);
+        b[r][i] = (__bf16)(float)((threadIdx.x * 7 + i) & 1);
+      }
+    }
   f32x16 c0, c1, c2, c3;
 #pragma unroll
   for (int i = 0; i < 16; ++i) c0[i] = c1[i] = c2[i] = c3[i] = 0.0f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
-      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
-      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[(u + 0) & 3], c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 1) & 3], b[(u + 2) & 3], c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 2) & 3], b[(u + 3) & 3], c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + 3) & 3], b[(u + 1) & 3], c3, 0, 0, 0);
     }
   }
   float s = 0.0f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
-  if (s == -1.0f) sink[0] = s;   // never true (all terms are non-negative)
+  if (s == 123456.789f) sink[0] = s;   // keeps the products alive; practically never taken
 }
 
 }  // namespace
@@ -79,13 +103,15 @@ int lfb_stream_read(const void* buf, size_t bytes, void* sink, void* hip_stream)
 }
 
 // 256 workgroups of 8 wavefronts, each wavefront issuing 16 * iters matrix instructions of
-// 2 * 32 * 32 * 16 FLOP.  *flop (host) receives the FLOP count of the launch.
-int lfb_mfma_loop(int iters, void* sink, double* flop, void* hip_stream) {
+// 2 * 32 * 32 * 16 FLOP, on constant (random_data = 0) or pseudo-random (1) operands.  *flop
+// (host) receives the FLOP count of the launch.
+int lfb_mfma_loop(int iters, int random_data, void* sink, double* flop, void* hip_stream) {
   if (!sink || iters < 1) return (int)hipErrorInvalidValue;
   if (flop) *flop = 256.0 * 8.0 * 16.0 * (double)iters * 2.0 * 32.0 * 32.0 * 16.0;
   void* args[] = {(void*)&sink, (void*)&iters};
-  return (int)hipLaunchKernel(reinterpret_cast<const void*>(mfma_loop_kernel), dim3(256), dim3(512),
-                              args, 0, (hipStream_t)hip_stream);
+  const void* fn = random_data ? reinterpret_cast<const void*>(mfma_loop_kernel<true>)
+                               : reinterpret_cast<const void*>(mfma_loop_kernel<false>);
+  return (int)hipLaunchKernel(fn, dim3(256), dim3(512), args, 0, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"
