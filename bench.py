@@ -350,6 +350,12 @@ def main():
                          "four kernels of the main path)")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip timing the step as one captured HIP graph")
+    ap.add_argument("--attn", choices=("one_pass", "split"), default="one_pass",
+                    help="attention call of the timed step: lf_sparse_attn (one list-driven kernel) or "
+                         "lf_sparse_attn_split (dense kernel over the current chunk + list-driven kernel)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the timed step: no cached selection, graph replay, pooling-only and split "
+                         "timings, per_config list, micro-benchmarks or CPU baseline (for profiler runs)")
     ap.add_argument("--sensitivity", action="store_true",
                     help="time the probe build of the attention kernel with extra work per unit "
                          "(prints its own JSON line and exits)")
@@ -361,6 +367,9 @@ def main():
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
     args = ap.parse_args()
+    if args.headline_only:
+        args.no_cached_select = args.no_graph = args.no_per_config = True
+        args.no_measured_peaks = args.no_cpu_baseline = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (heads would shard across GPUs "
                  "without communication; no multi-GPU figure is produced). Use --gpus 1.")
@@ -389,11 +398,19 @@ def main():
     nb = w.blocks_per_frame
     idx = torch.empty((w.heads, w.frames_per_chunk * nb, b.list_len), dtype=torch.int32, device="cuda")
     out = torch.empty_like(Q)
+    use_split = args.attn == "split" and bool(b.current_mandatory)
+    aws0 = torch.empty(lf.lf_attn_workspace_bytes(sh), dtype=torch.uint8, device="cuda") if use_split else None
+
+    def attend(bb):
+        if use_split:
+            lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, bb, O=out, workspace=aws0)
+        else:
+            lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
 
     def step():
         bb = lf.lf_chunk_budget(w.chunk_idx, sched)
         lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
-        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+        attend(bb)
 
     for _ in range(args.warmup):
         step()
@@ -414,7 +431,7 @@ def main():
         ev[i][0].record()
         lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
         ev[i][1].record()
-        lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+        attend(bb)
         ev[i][2].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -462,9 +479,11 @@ def main():
         "select_ms_median_min": [float(np.median(sel_all)), float(sel_all.min())],
         "attn_ms_median_min": [float(np.median(attn_all)), float(attn_all.min())],
         "kept_gflop": flops / 1e9, "tile_gflop": tile_flops / 1e9,
-        "roofline": {"kernel": "lf_attn_kernel", "bound": "mfma", "achieved": attn_tflops,
+        "roofline": {"kernel": "lf_attn_kernel (list-driven)" if not use_split else
+                               "lf_sparse_attn_split: dense + list-driven lf_attn_kernel launches together",
+                     "bound": "mfma", "achieved": attn_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": traffic.get("attn") if args.workload == "last_chunk" else None},
+                     "traffic": traffic.get("attn") if args.workload == "last_chunk" and not use_split else None},
         "select": {"bound": "hbm", "achieved": sel_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                    "frac": sel_gbps / PEAK_HBM_GBPS, "bytes": sel_bytes,
                    "traffic": traffic.get("select") if args.workload == "last_chunk" else None},
@@ -472,6 +491,9 @@ def main():
     }
     # the pooling pass alone (block and frame means of the whole cache, no Q, no scoring): the
     # HBM-bound part of mask selection on its own bytes
+    if args.headline_only:
+        print(json.dumps(res))
+        return
     kc_all = torch.empty(lf.lf_kcache_bytes(sh, w.frames), dtype=torch.uint8, device="cuda")
     pe = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
     for _ in range(5):
@@ -488,7 +510,7 @@ def main():
                         "ms": p_ms, "bytes": p_bytes, "achieved": p_bytes / (p_ms * 1e-3) / 1e9, "unit": "GB/s",
                         "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
     del kc_all
-    if b.current_mandatory:
+    if b.current_mandatory and not args.headline_only and not use_split:
         aws = torch.empty(lf.lf_attn_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
         se = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
         for _ in range(5):

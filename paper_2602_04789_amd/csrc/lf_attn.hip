@@ -91,8 +91,11 @@ template <int CH> __device__ __forceinline__ int v_swz(int row, int ch) {
 
 // Workgroup barrier that orders LDS accesses only; the global->LDS loads are waited for
 // explicitly (s_waitcnt vmcnt) by the wavefront that issued them, just before the barrier.
+// The tile loads are inline assembly that writes M0 and LDS, declared as such ("m0", "memory"),
+// so the compiler keeps LDS reads on their side of a load that reuses the buffer.
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0) only: no LDS read of this wavefront is still in flight
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
@@ -209,16 +212,16 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
                    "buffer_load_dwordx4 %2, %5, 0 offen offset:1024 lds\n\t"
                    "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 lds\n\t"
                    "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 lds"
-                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(rs));
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(rs) : "memory", "m0");
     else if constexpr (LPW == 2)
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                    "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
                    "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
-                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs));
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs) : "memory", "m0");
     else
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
                    "buffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(lds0), "v"(off[0]), "s"(rs));
+                   :: "s"(lds0), "v"(off[0]), "s"(rs) : "memory", "m0");
   };
   auto k_rsrc = [&](int2 e) { return tile_rsrc(Kh, (uint32_t)k_row_bytes, e); };
   auto v_rsrc = [&](int2 e) { return tile_rsrc(Vh, (uint32_t)v_row_bytes, e); };
