@@ -247,7 +247,15 @@ def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
         return float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
 
     sel_ms = timed(lambda: lf.lf_select_mask(Q, K, w.frame_len, w.block, b, indices=idx, workspace=ws))
-    attn_ms = timed(lambda: lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out))
+    one_pass = lambda: lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+    split = lambda: lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b, O=out, workspace=aws)
+    # the two attention calls are timed in alternating rounds, so that neither gets the cooler chip
+    rounds = [[], []]
+    for _ in range(3 if b.current_mandatory else 1):
+        rounds[0].append(timed(one_pass))
+        if b.current_mandatory:
+            rounds[1].append(timed(split))
+    attn_ms = float(np.mean(rounds[0]))
     lists = idx.cpu().numpy()
     flops = kept_flops(lists, w)
     sel_bytes = float((w.q_len + w.kv_len) * w.heads * w.head_dim * 2)
@@ -259,8 +267,7 @@ def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
            "select_gbps": sel_bytes / (sel_ms * 1e-3) / 1e9,
            "select_frac_of_hbm_peak": sel_bytes / (sel_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
     if b.current_mandatory:
-        res["attn_split_ms"] = timed(lambda: lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b,
-                                                                     O=out, workspace=aws))
+        res["attn_split_ms"] = float(np.mean(rounds[1]))
     if check_lists:
         ob = O.chunk_budget(w.chunk_idx, w.schedule)
         want = O.select_mask(synth.bf16_bits_to_f32(x["Q"]), synth.bf16_bits_to_f32(x["K"]),
