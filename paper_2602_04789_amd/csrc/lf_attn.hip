@@ -1,13 +1,12 @@
 // Blockwise sparse attention for gfx950 (Eq. 13; Eq. 3 and the paragraph after it: only
 // listed tiles are computed, the element mask is never materialised).
 //
-// One workgroup of two wavefronts per (head, query block of 64 rows), wavefront rh owning
-// query rows [32 rh, 32 rh + 32) with its own online-softmax state (m, l, O): nothing crosses
-// wavefronts, and there is no merge at the end.  Four workgroups share a compute unit, so
-// every SIMD holds two wavefronts of different workgroups, free to be in different parts of
-// their step (the matrix core of one beside the vector ALU of the other); the fewer
-// wavefronts a barrier ties together, the better that works (eight per workgroup measured
-// 9-13 % slower than four, two faster again).  Each listed KV block is taken as two half
+// Two wavefronts per (head, query block of 64 rows), wavefront rh owning query rows
+// [32 rh, 32 rh + 32) with its own online-softmax state (m, l, O): nothing crosses
+// wavefronts, and there is no merge at the end.  A workgroup holds two such query blocks and two
+// workgroups share a compute unit, so every SIMD holds two wavefronts, free to be in different
+// parts of their step (the matrix core of one beside the vector ALU of the other).  Each listed
+// KV block is taken as two half
 // tiles of 32 KV rows: the 32 x d K and V half tiles are brought into a double-buffered LDS
 // stage by asynchronous global->LDS loads, a wavefront's share of a half tile in one group
 // (V of the next step right after the barrier, K of the step after that after the first
@@ -101,31 +100,45 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // WAVES wavefronts of 32 query rows each per workgroup.  DENSE: the workgroup walks the KV
-// token range [kv0, kv1) and stores its state; otherwise it walks the list of its query block.
+// token range [kv0, kv1) and stores its state, all wavefronts sharing one tile stage.  Otherwise
+// it holds WAVES / 2 query blocks of two wavefronts each, every query block with a tile stage of
+// its own and walking its own list (two query blocks per workgroup measured 2 % faster than
+// one); the barriers are common, the lists being equally long.
 template <int D, int WAVES, bool DENSE>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs a) {
-  constexpr int kThreads = 64 * WAVES;
+  constexpr int QPW = DENSE ? 1 : WAVES / 2;    // query blocks per workgroup
+  constexpr int WPQ = WAVES / QPW;              // wavefronts that share one tile stage
+  constexpr int kThreads = 64 * WPQ;            // ... and their threads
   constexpr int CH = D / 8;                 // 16-byte chunks per token row
   constexpr int KS = D / 16;                // k-steps of S^T = K Q^T
   constexpr int MB = D / 32;                // 32-row blocks of O^T
   constexpr int RPI = 64 / CH;              // tile rows one wavefront load instruction covers
-  constexpr int LPW = 32 / (RPI * WAVES);   // load instructions per wavefront, per tile, per tensor
+  constexpr int LPW = 32 / (RPI * WPQ);     // load instructions per wavefront, per tile, per tensor
   constexpr int TILE = 32 * CH;             // uint4 per half tile (32 KV rows)
-  static_assert(LPW >= 1 && LPW * RPI * WAVES == 32, "a half tile must split evenly over the wavefronts");
+  static_assert(LPW >= 1 && LPW * RPI * WPQ == 32, "a half tile must split evenly over the wavefronts");
 
-  __shared__ uint4 buf0[2 * TILE];          // K | V of even tiles
-  __shared__ uint4 buf1[2 * TILE];          // K | V of odd tiles
-  __shared__ int2 ent[DENSE ? 1 : kMaxEnt / 2];   // (first token, token count) per list entry of a pass
+  __shared__ uint4 buf0_all[QPW][2 * TILE];          // K | V of even tiles
+  __shared__ uint4 buf1_all[QPW][2 * TILE];          // K | V of odd tiles
+  __shared__ int2 ent_all[QPW][DENSE ? 1 : kMaxEnt / 2];   // (first token, token count) per list entry of a pass
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
-  const int w = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
-  if (w >= a.total_wg) return;
+  const int wg = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  const int qb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) / WPQ;   // query block inside the workgroup
+  int w = wg * QPW + qb;
+  // A workgroup past the end leaves as a whole.  Inside the last one a query block past the end
+  // repeats the last valid one (it has to keep step at the barriers) and stores nothing.
+  if (wg * QPW >= a.total_wg) return;
+  const bool w_valid = w < a.total_wg;
+  w = min(w, a.total_wg - 1);
   const int per_head = DENSE ? a.wg_per_head : a.n_q;
   const int h = w / per_head, r = w % per_head;
+  uint4* const buf0 = buf0_all[qb];
+  uint4* const buf1 = buf1_all[qb];
+  int2* const ent = ent_all[qb];
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
+  const int tid = threadIdx.x % kThreads, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront inside its query block, in a scalar register
   const int rh = wave;
   const int ln = lane & 31, kg = lane >> 5;
 
@@ -523,7 +536,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   }
   // normalise and store
   const float inv = l_run > 0.0f ? 1.0f / l_run : 0.0f;   // a list without a valid id gives zero rows
-  if (qrow < q_cnt) {
+  if (qrow < q_cnt && w_valid) {
     uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -576,12 +589,14 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
   a.state_o = const_cast<float*>(state_o);
   a.state_ml = reinterpret_cast<float2*>(const_cast<float*>(state_ml));
   a.total_wg = dm->H * dm->n_q;
-  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  constexpr int kListWaves = 4;                  // two query blocks per workgroup
+  const int n_wg = (a.total_wg + kListWaves / 2 - 1) / (kListWaves / 2);
+  a.wg_per_xcd = (n_wg + 7) / 8;
   const unsigned grid = (unsigned)(a.wg_per_xcd * 8);
   hipStream_t st = (hipStream_t)stream;
   const hipError_t rc = dm->d == 128
-      ? lf_launch(lf_attn_kernel<128, 2, false>, dim3(grid), dim3(128), 0, st, a)
-      : lf_launch(lf_attn_kernel<64, 2, false>, dim3(grid), dim3(128), 0, st, a);
+      ? lf_launch(lf_attn_kernel<128, kListWaves, false>, dim3(grid), dim3(64 * kListWaves), 0, st, a)
+      : lf_launch(lf_attn_kernel<64, kListWaves, false>, dim3(grid), dim3(64 * kListWaves), 0, st, a);
   return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
 }
 
