@@ -350,6 +350,54 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, lists: np.ndar
     return O
 
 
+def sparse_attention_backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, dO: np.ndarray,
+                              lists: np.ndarray, frame_len: int, block: int,
+                              scale: Optional[float] = None):
+    """Gradients of Eq. 13 with respect to Q, K and V for an upstream gradient dO of O
+    (the paper finetunes with the sparse mask in place, which needs exactly this).
+
+    For a query row x of block r with kept columns Y_r, s_xy = scale q_x.k_y,
+    p = softmax_y(s), o_x = sum_y p_xy v_y.  By the chain rule
+        dV_y  = sum_x p_xy dO_x
+        dp_xy = dO_x . v_y,   delta_x = sum_y p_xy dp_xy  (= dO_x . o_x)
+        ds_xy = p_xy (dp_xy - delta_x)
+        dQ_x  = scale sum_y ds_xy k_y,   dK_y = scale sum_x ds_xy q_x
+    summed over every (x, y) pair the lists keep; an id listed twice counts twice, as in the
+    forward pass.  All in binary64.  Returns (dQ [H, L_q, d], dK [H, L_k, d], dV [H, L_k, d]).
+    """
+    H, Lq, d = Q.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(float(d))
+    nb = -(-frame_len // block)
+    n_q = (Lq // frame_len) * nb
+    dQ = np.zeros((H, Lq, d), dtype=np.float64)
+    dK = np.zeros((H, K.shape[1], d), dtype=np.float64)
+    dV = np.zeros((H, K.shape[1], d), dtype=np.float64)
+    for h in range(H):
+        for r in range(n_q):
+            qlo, qhi = block_token_range(r, frame_len, block)
+            cols: List[int] = []
+            for c in lists[h, r]:
+                lo, hi = block_token_range(c, frame_len, block)
+                cols.extend(range(lo, hi))
+            cols_a = np.asarray(cols, dtype=np.int64)
+            q = Q[h, qlo:qhi].astype(np.float64)
+            k = K[h][cols_a].astype(np.float64)
+            v = V[h][cols_a].astype(np.float64)
+            do = dO[h, qlo:qhi].astype(np.float64)
+            s = (q @ k.T) * scale
+            s -= s.max(axis=1, keepdims=True)
+            e = np.exp(s)
+            p = e / e.sum(axis=1, keepdims=True)
+            dp = do @ v.T
+            delta = (p * dp).sum(axis=1, keepdims=True)
+            ds = p * (dp - delta)
+            dQ[h, qlo:qhi] += scale * (ds @ k)
+            np.add.at(dK[h], cols_a, scale * (ds.T @ q))     # add.at: a column may be listed twice
+            np.add.at(dV[h], cols_a, p.T @ do)
+    return dQ, dK, dV
+
+
 def full_lists(heads: int, frame_len: int, block: int, f: int, F: int) -> np.ndarray:
     """The all-ones block mask as index lists (full budget)."""
     nb = -(-frame_len // block)

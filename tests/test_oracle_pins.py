@@ -439,3 +439,86 @@ def test_attention_scale_is_inverse_sqrt_d():
     Ob = O.sparse_attention_block(Q[0], K[0], V[0], 0, [0, 1], 1, 64)
     want = 1.0 / (1.0 + math.exp(-(2.0 - (-2.0)) / math.sqrt(d)))
     assert abs(Ob[0, 0] - want) < 1e-15
+
+
+# ----------------------------------------------------------------------------- backward of Eq. 13
+
+def _bwd_case(seed=0, heads=2, frame_len=40, block=16, f=1, F=3, d=8, keep=3):
+    rng = np.random.default_rng(seed)
+    Lq, Lk = f * frame_len, F * frame_len
+    Q = rng.standard_normal((heads, Lq, d))
+    K = rng.standard_normal((heads, Lk, d))
+    V = rng.standard_normal((heads, Lk, d))
+    dO = rng.standard_normal((heads, Lq, d))
+    nb = -(-frame_len // block)
+    lists = np.stack([np.stack([np.sort(rng.choice(F * nb, size=keep, replace=False))
+                                for _ in range(f * nb)]) for _ in range(heads)]).astype(np.int32)
+    return Q, K, V, dO, lists, frame_len, block
+
+
+def _dense_mask(lists, frame_len, block, Lq, Lk):
+    H, n_q, _ = lists.shape
+    M = np.zeros((H, Lq, Lk), dtype=bool)
+    for h in range(H):
+        for r in range(n_q):
+            qlo, qhi = O.block_token_range(r, frame_len, block)
+            for c in lists[h, r]:
+                lo, hi = O.block_token_range(c, frame_len, block)
+                M[h, qlo:qhi, lo:hi] = True
+    return M
+
+
+def test_backward_matches_library_autodiff_of_masked_dense_attention():
+    """torch autograd (binary64) through softmax(QK^T scale + mask) V, an independent derivation."""
+    Q, K, V, dO, lists, n, b = _bwd_case()
+    M = torch.from_numpy(_dense_mask(lists, n, b, Q.shape[1], K.shape[1]))
+    q, k, v = (torch.tensor(t, dtype=torch.float64, requires_grad=True) for t in (Q, K, V))
+    scale = 1.0 / math.sqrt(Q.shape[2])
+    s = (q @ k.transpose(1, 2)) * scale
+    s = s.masked_fill(~M, float("-inf"))
+    o = torch.softmax(s, dim=-1) @ v
+    o.backward(torch.from_numpy(dO))
+    dQ, dK, dV = O.sparse_attention_backward(Q, K, V, dO, lists, n, b)
+    assert np.allclose(dQ, q.grad.numpy(), atol=1e-12)
+    assert np.allclose(dK, k.grad.numpy(), atol=1e-12)
+    assert np.allclose(dV, v.grad.numpy(), atol=1e-12)
+
+
+def test_backward_matches_finite_differences_of_the_forward_oracle():
+    Q, K, V, dO, lists, n, b = _bwd_case(seed=3, heads=1, frame_len=20, block=8, F=2, d=4, keep=2)
+    dQ, dK, dV = O.sparse_attention_backward(Q, K, V, dO, lists, n, b)
+    loss = lambda q, k, v: float((O.sparse_attention(q, k, v, lists, n, b) * dO).sum())
+    rng = np.random.default_rng(0)
+    eps = 1e-6
+    for name, T, G in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for _ in range(6):
+            idx = tuple(int(rng.integers(s)) for s in T.shape)
+            Tp, Tm = T.copy(), T.copy()
+            Tp[idx] += eps
+            Tm[idx] -= eps
+            args = {"Q": (Tp, K, V), "K": (Q, Tp, V), "V": (Q, K, Tp)}[name]
+            argm = {"Q": (Tm, K, V), "K": (Q, Tm, V), "V": (Q, K, Tm)}[name]
+            fd = (loss(*args) - loss(*argm)) / (2 * eps)
+            assert abs(fd - G[idx]) < 1e-6, (name, idx, fd, G[idx])
+
+
+def test_backward_invariants_and_duplicates():
+    Q, K, V, dO, lists, n, b = _bwd_case(seed=5)
+    dQ, dK, dV = O.sparse_attention_backward(Q, K, V, dO, lists, n, b)
+    # softmax rows sum to one: the V gradients add up to the upstream gradients ...
+    assert np.allclose(dV.sum(axis=1), dO.sum(axis=1), atol=1e-12)
+    # ... and a common shift of all keys changes nothing: the K gradients add up to zero
+    assert np.allclose(dK.sum(axis=1), 0.0, atol=1e-12)
+    # keys no list mentions get no gradient
+    M = _dense_mask(lists, n, b, Q.shape[1], K.shape[1])
+    unused = ~M.any(axis=1)
+    assert np.all(dK[unused] == 0.0) and np.all(dV[unused] == 0.0) and unused.any()
+    # an id listed twice counts twice, as in the forward pass: its tokens appear twice among the columns
+    twice = lists.copy()
+    twice[:, :, 1] = twice[:, :, 0]
+    dQ2, dK2, dV2 = O.sparse_attention_backward(Q, K, V, dO, twice, n, b)
+    out2 = O.sparse_attention(Q, K, V, twice, n, b)
+    eps = 1e-6
+    Vp = V.copy(); Vp[0, O.block_token_range(twice[0, 0, 0], n, b)[0], 0] += eps
+    fd = ((O.sparse_attention(Q, K, Vp, twice, n, b) - out2) * dO).sum() / eps
+    assert abs(fd - dV2[0, O.block_token_range(twice[0, 0, 0], n, b)[0], 0]) < 1e-5
