@@ -233,6 +233,49 @@ int lf_sparse_attn_split(const void* Q, const void* Kcache, const void* Vcache,
                          void* hip_stream);
 
 /*
+ * Training pair for the blockwise sparse attention (Eq. 13; the paper finetunes the generator
+ * with the sparse mask in place, Sec. 5 "Experimental Details", which needs the gradient of
+ * Eq. 13 through the kept tiles; the lists themselves carry no gradient).
+ *
+ * lf_sparse_attn_fwd is lf_sparse_attn that also leaves, per query row x,
+ *   lse2_x = log2 sum_y exp2(q_x . k_y * softmax_scale * log2 e)   over the row's kept tokens
+ * (float32 [H][q_len], contiguous; +inf for a row whose list holds no valid id).
+ *
+ * lf_sparse_attn_bwd computes, for an upstream gradient dO and with p_xy = exp2(s_xy log2 e -
+ * lse2_x), s_xy = softmax_scale q_x . k_y, delta_x = dO_x . O_x:
+ *   dV_y = sum_x p_xy dO_x
+ *   dQ_x = softmax_scale sum_y p_xy (dO_x . v_y - delta_x) k_y
+ *   dK_y = softmax_scale sum_x p_xy (dO_x . v_y - delta_x) q_x
+ * the sums running over exactly the (query block, KV block) tiles the lists keep.  bf16 MFMA
+ * products (p and p (dp - delta) are rounded to bfloat16 before the accumulating products),
+ * float32 accumulation in a fixed order (no atomics: results are reproducible), bfloat16 output.
+ * Arguments
+ *   Q, Kcache, Vcache, shape, softmax_scale   as in the forward call.
+ *   O, dO          device, bfloat16 [H][q_len][d], both with the o_ strides; O as the forward
+ *                  call wrote it.
+ *   lse2           device, float32 [H][q_len], as the forward call wrote it.
+ *   indices        device, int32 [H][n_q][list_len], the forward call's lists.  Every list must
+ *                  be ascending without duplicates among its valid ids (what lf_select_mask
+ *                  writes); this is not checked, and other lists give wrong dK and dV.  Ids
+ *                  outside [0, n_k) are skipped.
+ *   dQ             device, bfloat16, written, with the q_ strides.
+ *   dK, dV         device, bfloat16, written for every KV token (zeros where no list keeps the
+ *                  token's block), with the k_ and v_ strides.
+ *   workspace      device scratch of >= lf_attn_bwd_workspace_bytes(shape), 256-byte aligned;
+ *                  holds delta and the transposed lists during the call.
+ * Errors: as lf_sparse_attn; LF_ERR_WORKSPACE.
+ */
+int lf_sparse_attn_fwd(const void* Q, const void* Kcache, const void* Vcache,
+                       const lf_shape* shape, const int32_t* indices, int32_t list_len,
+                       float softmax_scale, void* O, float* lse2, void* hip_stream);
+size_t lf_attn_bwd_workspace_bytes(const lf_shape* shape);
+int lf_sparse_attn_bwd(const void* Q, const void* Kcache, const void* Vcache, const void* O,
+                       const void* dO, const float* lse2, const lf_shape* shape,
+                       const int32_t* indices, int32_t list_len, float softmax_scale,
+                       void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
+/*
  * Pooled-key cache (an extension the paper does not describe; it follows from its setting).
  * The keys of a finished chunk never change again (Sec. 3: the rollout appends each generated
  * chunk's K/V to the cache and later chunks only read it), so their block means and frame means

@@ -25,7 +25,7 @@ def probe_lib(tag: str) -> str:
     return os.path.join(PKG, f"liblf_hsa_probe_{tag}.so")
 OBJ = os.path.join(PKG, "_build")
 
-SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip", "lf_producer.hip"]
+SOURCES = ["lf_host.cpp", "lf_select.hip", "lf_attn.hip", "lf_attn_bwd.hip", "lf_producer.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -62,6 +62,9 @@ struct AttnArgs {
   // state_o is not null.
   float* state_o;
   float2* state_ml;
+  // list-driven kernel, optional: log2 of the row's sum of exp2(s c) over its kept columns,
+  // float32 [H][q_len] (+inf for a row without a kept column), for the backward pass
+  float* lse2;
   // dense kernel only: query rows per workgroup, workgroups per head, KV token range
   int q_len, rows_per_wg, wg_per_head, kv0, kv1;
 };
@@ -537,6 +540,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   // normalise and store
   const float inv = l_run > 0.0f ? 1.0f / l_run : 0.0f;   // a list without a valid id gives zero rows
   if (qrow < q_cnt && w_valid) {
+    if (a.lse2 != nullptr && kg == 0)
+      a.lse2[(int64_t)h * a.q_len + qtok0 + qrow] = l_run > 0.0f ? m_run + __builtin_log2f(l_run) : INFINITY;
     uint16_t* op = a.O + (int64_t)h * a.o_stride_head + (int64_t)(qtok0 + qrow) * a.o_stride_tok;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -580,9 +585,11 @@ static AttnArgs attn_args(const void* Q, const void* K, const void* V, const lf_
 // entries apart); with a state (state_o, state_ml) it continues that online softmax.
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
                    const lf_dims* dm, const int32_t* indices, int32_t list_len, int32_t list_stride,
-                   float scale, void* O, const float* state_o, const float* state_ml, void* stream) {
+                   float scale, void* O, const float* state_o, const float* state_ml, float* lse2,
+                   void* stream) {
   AttnArgs a = attn_args(Q, K, V, s, dm, scale);
   a.O = (uint16_t*)O;
+  a.lse2 = lse2;
   a.idx = indices;
   a.list_len = list_len;
   a.list_stride = list_stride;

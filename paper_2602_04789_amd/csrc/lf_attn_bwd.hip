@@ -1,0 +1,426 @@
+// Backward pass of the blockwise sparse attention (Eq. 13) for gfx950: gradients with respect
+// to Q, K and V for an upstream gradient dO, over exactly the tiles the index lists keep
+// (the paper finetunes with the sparse mask in place, Sec. 5 "Experimental Details").
+//
+// With s_xy = scale q_x.k_y, p = softmax over the kept columns, o = p v:
+//     dV_y = sum_x p_xy dO_x          dp_xy = dO_x . v_y      delta_x = dO_x . o_x
+//     ds_xy = p_xy (dp_xy - delta_x)  dQ_x = scale sum_y ds_xy k_y    dK_y = scale sum_x ds_xy q_x
+// p is rebuilt from the row's log-sum-exp, which the training forward call leaves (in the exp2
+// domain: lse2_x = log2 sum_y exp2(s_xy log2 e)), so no row maximum or sum is needed here.
+//
+// No atomics and a fixed summation order: two passes of one kernel template, each owning its
+// outputs.  Pass 1 is query-major (a workgroup owns a query block, walks its list of KV blocks,
+// keeps dQ in registers); pass 2 is key-major (a workgroup owns a KV block, walks the list of
+// query blocks that keep it -- the transposed lists, made by a small kernel -- and keeps dK and
+// dV in registers).  Both recompute the scores of a tile; in both the products are arranged as
+// in the forward kernel: the "score-like" products S' = A1 X^T and dP' = A2 Y^T take their A
+// operand from a 32-row tile in LDS (row reads) and their B operand from registers that hold the
+// owner block, which leaves a lane with one owner column and 16 stream rows; P' and dS' are then
+// already in the B-operand layout of the accumulating products, whose A operand is the same tile
+// read through the transposing LDS read.
+//     pass 1: owner = query block (X = Q, Y = dO), stream = KV blocks (A1 = K, A2 = V),
+//             dQ^T += K^T dS'
+//     pass 2: owner = KV block (X = K, Y = V), stream = query blocks (A1 = Q, A2 = dO),
+//             dV^T += dO^T P',  dK^T += Q^T dS'
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "lf_common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int int32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 128;    // two wavefronts of 32 owner rows each
+constexpr int kPass = 256;       // list entries decoded per pass
+
+struct BwdArgs {
+  const uint16_t* X;     // owner-side operand of the scores (Q in pass 1, K in pass 2)
+  const uint16_t* Y;     // owner-side operand of dP (dO in pass 1, V in pass 2)
+  const uint16_t* A1;    // streamed operand of the scores (K in pass 1, Q in pass 2)
+  const uint16_t* A2;    // streamed operand of dP (V in pass 1, dO in pass 2)
+  uint16_t* out1;        // dQ (pass 1) or dK (pass 2): scale * sum of A1^T dS'
+  uint16_t* out2;        // dV (pass 2 only): sum of A2^T P'
+  const float* lse2;     // [H][q_len]
+  const float* delta;    // [H][q_len]
+  const int32_t* idx;    // lists: [H][owners][list_stride]
+  const int32_t* cnt;    // entries per list, or null: list_len for all
+  int64_t x_tok, x_head, y_tok, y_head, a1_tok, a1_head, a2_tok, a2_head;
+  int64_t o1_tok, o1_head, o2_tok, o2_head;
+  int n, nb, owners, streams, list_len, list_stride, q_len;
+  int total_wg, wg_per_xcd;
+  float c, scale;
+};
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+};
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// One swizzle for both tiles of a step: it has to serve row reads (16 bytes per lane, 32
+// consecutive rows) and the transposing reads (32 bytes from each of four consecutive rows per
+// group of 16 lanes); shifting each of eight consecutive rows by two 16-byte chunks does.
+template <int CH> __device__ __forceinline__ int swz(int row, int ch) {
+  return CH == 16 ? ch ^ ((row & 7) << 1) : ch ^ ((row & 1) << 2);
+}
+
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+// KVMAJOR = false: pass 1 (owner = query block); true: pass 2 (owner = KV block).
+template <int D, bool KVMAJOR>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, KVMAJOR ? 1 : 2)))
+void lf_attn_bwd_kernel(BwdArgs a) {
+  constexpr int CH = D / 8;
+  constexpr int KS = D / 16;
+  constexpr int MB = D / 32;
+  constexpr int RPI = 64 / CH;
+  constexpr int LPW = 32 / (RPI * 2);
+  constexpr int TILE = 32 * CH;             // uint4 per 32-row tile
+
+  __shared__ uint4 buf[2][2 * TILE];        // [step parity][A1 tile | A2 tile]
+  __shared__ int2 ent[kPass];               // (first token, token count) per list entry of a pass
+  __shared__ float2 st[2][32];              // pass 2: (lse2, delta) of the 32 streamed query rows
+
+  const int w = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  if (w >= a.total_wg) return;
+  const int h = w / a.owners, r = w % a.owners;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31, kg = lane >> 5;
+
+  // owner block: tokens [otok0, otok0 + o_cnt); this lane's owner row (a column of S')
+  const int otok0 = (r / a.nb) * a.n + (r % a.nb) * 64;
+  const int o_cnt = min(64, a.n - (r % a.nb) * 64);
+  const int orow = 32 * wave + ln;
+  const bool o_ok = orow < o_cnt;
+
+  const int32_t* list = a.idx + ((int64_t)h * a.owners + r) * a.list_stride;
+  const int n_ent = a.cnt ? a.cnt[(int64_t)h * a.owners + r] : a.list_len;
+
+  // B operands: lane (column ln, k-group kg) holds 8 consecutive channels of its owner row
+  Frag xf[KS], yf[KS];
+  {
+    const uint16_t* xp = a.X + (int64_t)h * a.x_head + (int64_t)(otok0 + orow) * a.x_tok;
+    const uint16_t* yp = a.Y + (int64_t)h * a.y_head + (int64_t)(otok0 + orow) * a.y_tok;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      xf[s].u = o_ok ? *reinterpret_cast<const uint4*>(xp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
+      yf[s].u = o_ok ? *reinterpret_cast<const uint4*>(yp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
+    }
+  }
+  // pass 1: the query row of this lane; its log-sum-exp and delta (a row outside the block gets
+  // +inf, which makes all its probabilities zero)
+  float my_lse = INFINITY, my_delta = 0.0f;
+  if (!KVMAJOR && o_ok) {
+    my_lse = a.lse2[(int64_t)h * a.q_len + otok0 + orow];
+    my_delta = a.delta[(int64_t)h * a.q_len + otok0 + orow];
+  }
+
+  const char* A1h = reinterpret_cast<const char*>(a.A1 + (int64_t)h * a.a1_head);
+  const char* A2h = reinterpret_cast<const char*>(a.A2 + (int64_t)h * a.a2_head);
+  const uint32_t a1_row_bytes = (uint32_t)(a.a1_tok * 2), a2_row_bytes = (uint32_t)(a.a2_tok * 2);
+
+  // tile loads, global -> LDS (see the forward kernel): load i of wavefront `wave` fills rows
+  // [RPI (LPW wave + i), +RPI); the buffer resource is the tile itself, so rows past the count
+  // read as zeros and ids outside the tensor become empty tiles
+  const int ld_r = lane / CH, ld_p = lane % CH;
+  uint32_t off1[LPW], off2[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int row = RPI * (LPW * wave + i) + ld_r;
+    off1[i] = (uint32_t)row * a1_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
+    off2[i] = (uint32_t)row * a2_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
+  }
+  auto rsrc = [](const char* base, uint32_t row_bytes, int2 e) {
+    int32x4 rs;
+    const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)e.x * row_bytes;
+    rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    rs[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
+    rs[2] = __builtin_amdgcn_readfirstlane((int)((uint32_t)e.y * row_bytes));
+    rs[3] = 0x00020000;
+    return rs;
+  };
+  auto fetch = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW]) __attribute__((always_inline)) {
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
+    if constexpr (LPW == 4)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %5, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %5, 0 offen offset:1024 lds\n\t"
+                   "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 lds\n\t"
+                   "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 lds"
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(rs) : "memory", "m0");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs) : "memory", "m0");
+  };
+  // half tile t of the pass: list entry t/2, rows [32 (t&1), +32) of its block
+  auto half = [&](int t, int l1_local) {
+    const int2 e = ent[min(t >> 1, l1_local - 1)];
+    const int2 u = make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+    return (t & 1) ? make_int2(u.x + 32, max(u.y - 32, 0)) : make_int2(u.x, min(u.y, 32));
+  };
+
+  // LDS addresses of this lane's fragments (loop invariants): row reads of row ln, chunk 2s+kg
+  int raddr[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) raddr[s] = ln * CH + swz<CH>(ln, 2 * s + kg);
+  // transposing reads (see the forward kernel), in bf16 elements
+  int tbase[MB];
+  {
+    const int i16 = lane & 15;
+    const int tr_row = 4 * kg + (i16 >> 2);
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int col = 32 * mb + tr_col;
+      tbase[mb] = (tr_row * CH + swz<CH>(tr_row, col >> 3)) * 8 + (col & 7);
+    }
+  }
+  auto tfrag = [&](const uint4* tile, int u, int mb) __attribute__((always_inline)) {
+    const uint16_t* p16 = reinterpret_cast<const uint16_t*>(tile);
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p16 + tbase[mb] + (16 * u) * CH * 8));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p16 + tbase[mb] + (16 * u + 8) * CH * 8));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+
+  f32x16 acc1[MB], acc2[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc1[mb][i] = acc2[mb][i] = 0.0f;
+  f32x16 zero16;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
+
+  for (int l0 = 0; l0 < n_ent; l0 += kPass) {
+    const int l1 = min(n_ent, l0 + kPass);
+    const int n_local = l1 - l0, steps = 2 * n_local;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    for (int i = tid; i < n_local; i += kThreads) {
+      const int cidx = list[l0 + i];
+      const bool ok = (unsigned)cidx < (unsigned)a.streams;
+      const int tau = ok ? cidx / a.nb : 0, j = ok ? cidx % a.nb : 0;
+      ent[i] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+    }
+    __syncthreads();
+
+    // step t uses buf[t & 1]; its tiles are requested one step ahead
+    float2 st_next = make_float2(INFINITY, 0.0f);
+    auto request = [&](int t) __attribute__((always_inline)) {
+      const int2 e = half(t, n_local);
+      fetch(rsrc(A1h, a1_row_bytes, e), buf[t & 1], off1);
+      fetch(rsrc(A2h, a2_row_bytes, e), buf[t & 1] + TILE, off2);
+      if (KVMAJOR && tid < 32) {
+        st_next = make_float2(INFINITY, 0.0f);
+        if (tid < e.y) {
+          st_next.x = a.lse2[(int64_t)h * a.q_len + e.x + tid];
+          st_next.y = a.delta[(int64_t)h * a.q_len + e.x + tid];
+        }
+      }
+    };
+    request(0);
+    for (int t = 0; t < steps; ++t) {
+      uint4* cur = buf[t & 1];
+      const int cnt = half(t, n_local).y;
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      if (KVMAJOR && tid < 32) st[t & 1][tid] = st_next;
+      lds_barrier();
+      if (t + 1 < steps) request(t + 1);
+
+      // S'[stream row, owner column] and dP' of this wavefront's 32 x 32 tile
+      f32x16 sacc = zero16, pacc = zero16;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        Frag f1, f2;
+        f1.u = cur[raddr[s]];
+        f2.u = cur[TILE + raddr[s]];
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.v, xf[s].v, sacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2.v, yf[s].v, pacc, 0, 0, 0);
+      }
+      // P' = exp2(s c - lse2), dS' = P' (dP' - delta), both packed to bfloat16 in the B-operand
+      // layout of the accumulating products; accumulator i is stream row 8 (i/4) + 4 kg + i%4
+      bf16x8 pf[2], dsf[2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = 8 * (i >> 2) + 4 * kg + (i & 3);
+        float lse = my_lse, dl = my_delta;
+        if (KVMAJOR) {
+          const float2 sd = st[t & 1][row];
+          lse = sd.x;
+          dl = sd.y;
+        }
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse));
+        if (row >= cnt) p = 0.0f;
+        pf[i >> 3][i & 7] = (__bf16)p;
+        dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - dl));
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const bf16x8 t1 = tfrag(cur, u, mb);
+          acc1[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, dsf[u], acc1[mb], 0, 0, 0);
+          if (KVMAJOR) {
+            const bf16x8 t2 = tfrag(cur + TILE, u, mb);
+            acc2[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, pf[u], acc2[mb], 0, 0, 0);
+          }
+        }
+    }
+  }
+
+  // accumulator i of acc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of the owner row
+  if (o_ok) {
+    uint16_t* p1 = a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc1[mb][4 * g + e] * a.scale);
+        *reinterpret_cast<bf16x4*>(p1 + 32 * mb + 8 * g + 4 * kg) = o4;
+      }
+    if (KVMAJOR) {
+      uint16_t* p2 = a.out2 + (int64_t)h * a.o2_head + (int64_t)(otok0 + orow) * a.o2_tok;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (__bf16)acc2[mb][4 * g + e];
+          *reinterpret_cast<bf16x4*>(p2 + 32 * mb + 8 * g + 4 * kg) = o4;
+        }
+    }
+  }
+}
+
+// delta_x = dO_x . O_x (float32), one 16-lane group per row.
+template <int D>
+__global__ __launch_bounds__(256) void lf_attn_delta_kernel(const uint16_t* __restrict__ O,
+                                                            const uint16_t* __restrict__ dO,
+                                                            float* __restrict__ delta, int64_t o_tok,
+                                                            int64_t o_head, int q_len, int rows) {
+  constexpr int LPR = D / 8;                  // lanes per row
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  const int row = gid / LPR, ch = gid % LPR;
+  float s = 0.0f;
+  if (row < rows) {
+    const int h = row / q_len, x = row % q_len;
+    const int64_t off = (int64_t)h * o_head + (int64_t)x * o_tok + ch * 8;
+    const uint4 u = *reinterpret_cast<const uint4*>(O + off), v = *reinterpret_cast<const uint4*>(dO + off);
+    const uint32_t uu[4] = {u.x, u.y, u.z, u.w}, vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s = fmaf(__uint_as_float(uu[i] << 16), __uint_as_float(vv[i] << 16), s);
+      s = fmaf(__uint_as_float(uu[i] & 0xffff0000u), __uint_as_float(vv[i] & 0xffff0000u), s);
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o);
+  if (row < rows && ch == 0) delta[row] = s;
+}
+
+// Transposed lists: for every (head, KV block c) the query blocks whose list holds c, ascending.
+// One thread per (head, c); every list is searched by bisection (lists are ascending).
+__global__ void lf_transpose_lists_kernel(const int32_t* __restrict__ idx, int32_t* __restrict__ tlist,
+                                          int32_t* __restrict__ tcnt, int heads, int n_q, int n_k,
+                                          int list_len) {
+  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= heads * n_k) return;
+  const int h = gid / n_k, c = gid % n_k;
+  int32_t* out = tlist + (int64_t)gid * n_q;
+  int cnt = 0;
+  for (int r = 0; r < n_q; ++r) {
+    const int32_t* l = idx + ((int64_t)h * n_q + r) * list_len;
+    int lo = 0, hi = list_len;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (l[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    if (lo < list_len && l[lo] == c) out[cnt++] = r;
+  }
+  tcnt[gid] = cnt;
+}
+
+}  // namespace
+
+int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                       const float* lse2, const lf_shape* s, const lf_dims* dm, const int32_t* indices,
+                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* delta,
+                       int32_t* tlist, int32_t* tcnt, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int q_len = dm->f * dm->n;
+  const int rows = dm->H * q_len;
+  {
+    const int lanes = rows * (dm->d / 8);
+    const unsigned grid = (unsigned)((lanes + 255) / 256);
+    const hipError_t rc = dm->d == 128
+        ? lf_launch(lf_attn_delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const uint16_t*)O,
+                    (const uint16_t*)dO, delta, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows)
+        : lf_launch(lf_attn_delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const uint16_t*)O,
+                    (const uint16_t*)dO, delta, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows);
+    if (rc != hipSuccess) return LF_ERR_HIP;
+  }
+  {
+    const unsigned grid = (unsigned)((dm->H * dm->n_k + 255) / 256);
+    if (lf_launch(lf_transpose_lists_kernel, dim3(grid), dim3(256), 0, st, indices, tlist, tcnt, dm->H,
+                  dm->n_q, dm->n_k, (int)list_len) != hipSuccess)
+      return LF_ERR_HIP;
+  }
+  BwdArgs a = {};
+  a.lse2 = lse2;
+  a.delta = delta;
+  a.n = dm->n;
+  a.nb = dm->nb;
+  a.q_len = q_len;
+  a.c = scale * 1.4426950408889634f;
+  a.scale = scale;
+  // pass 1: dQ
+  a.X = (const uint16_t*)Q;   a.x_tok = s->q_stride_tok;  a.x_head = s->q_stride_head;
+  a.Y = (const uint16_t*)dO;  a.y_tok = s->o_stride_tok;  a.y_head = s->o_stride_head;
+  a.A1 = (const uint16_t*)K;  a.a1_tok = s->k_stride_tok; a.a1_head = s->k_stride_head;
+  a.A2 = (const uint16_t*)V;  a.a2_tok = s->v_stride_tok; a.a2_head = s->v_stride_head;
+  a.out1 = (uint16_t*)dQ;     a.o1_tok = s->q_stride_tok; a.o1_head = s->q_stride_head;
+  a.out2 = nullptr;
+  a.idx = indices; a.cnt = nullptr; a.list_len = list_len; a.list_stride = list_len;
+  a.owners = dm->n_q; a.streams = dm->n_k;
+  a.total_wg = dm->H * dm->n_q;
+  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  hipError_t rc = dm->d == 128
+      ? lf_launch(lf_attn_bwd_kernel<128, false>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
+      : lf_launch(lf_attn_bwd_kernel<64, false>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
+  if (rc != hipSuccess) return LF_ERR_HIP;
+  // pass 2: dK, dV
+  a.X = (const uint16_t*)K;   a.x_tok = s->k_stride_tok;  a.x_head = s->k_stride_head;
+  a.Y = (const uint16_t*)V;   a.y_tok = s->v_stride_tok;  a.y_head = s->v_stride_head;
+  a.A1 = (const uint16_t*)Q;  a.a1_tok = s->q_stride_tok; a.a1_head = s->q_stride_head;
+  a.A2 = (const uint16_t*)dO; a.a2_tok = s->o_stride_tok; a.a2_head = s->o_stride_head;
+  a.out1 = (uint16_t*)dK;     a.o1_tok = s->k_stride_tok; a.o1_head = s->k_stride_head;
+  a.out2 = (uint16_t*)dV;     a.o2_tok = s->v_stride_tok; a.o2_head = s->v_stride_head;
+  a.idx = tlist; a.cnt = tcnt; a.list_len = dm->n_q; a.list_stride = dm->n_q;
+  a.owners = dm->n_k; a.streams = dm->n_q;
+  a.total_wg = dm->H * dm->n_k;
+  a.wg_per_xcd = (a.total_wg + 7) / 8;
+  rc = dm->d == 128
+      ? lf_launch(lf_attn_bwd_kernel<128, true>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
+      : lf_launch(lf_attn_bwd_kernel<64, true>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
+  return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
+}

@@ -43,7 +43,12 @@ int lf_launch_qk_norm_rope(const void* X, const float* g, const float* cosv, con
 int lf_static_scratch(void** ptr);
 int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* s,
                    const lf_dims* dm, const int32_t* indices, int32_t list_len, int32_t list_stride,
-                   float scale, void* O, const float* state_o, const float* state_ml, void* stream);
+                   float scale, void* O, const float* state_o, const float* state_ml, float* lse2,
+                   void* stream);
+int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                       const float* lse2, const lf_shape* s, const lf_dims* dm, const int32_t* indices,
+                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* delta,
+                       int32_t* tlist, int32_t* tcnt, void* stream);
 int lf_launch_attn_dense(const void* Q, const void* K, const void* V, const lf_shape* s,
                          const lf_dims* dm, int kv0, int kv1, float scale, float* state_o,
                          float* state_ml, void* stream);

@@ -312,7 +312,8 @@ extern "C" int lf_sparse_attn(const void* Q, const void* K, const void* V, const
       misaligned(indices, 4))
     return LF_ERR_ALIGN;
   float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
-  return lf_launch_attn(Q, K, V, s, &dm, indices, list_len, list_len, scale, O, nullptr, nullptr, stream);
+  return lf_launch_attn(Q, K, V, s, &dm, indices, list_len, list_len, scale, O, nullptr, nullptr, nullptr,
+                        stream);
 }
 
 // Scratch of lf_sparse_attn_split: O state float32 [H][q_len][d], then (m, l) float32 [H][q_len][2].
@@ -343,7 +344,7 @@ extern "C" int lf_sparse_attn_split(const void* Q, const void* K, const void* V,
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
   if (!b->current_mandatory)   // nothing is common to all query blocks: one list-driven pass
     return lf_launch_attn(Q, K, V, s, &dm, indices, b->list_len, b->list_len, scale, O, nullptr,
-                          nullptr, stream);
+                          nullptr, nullptr, stream);
   size_t off_ml = 0;
   const size_t need = attn_state_bytes(dm, &off_ml);
   if (!workspace || workspace_bytes < need) return LF_ERR_WORKSPACE;
@@ -353,7 +354,65 @@ extern "C" int lf_sparse_attn_split(const void* Q, const void* K, const void* V,
   rc = lf_launch_attn_dense(Q, K, V, s, &dm, dm.F_h * dm.n, dm.F * dm.n, scale, state_o, state_ml, stream);
   if (rc != LF_OK) return rc;
   return lf_launch_attn(Q, K, V, s, &dm, indices, b->k_blocks, b->list_len, scale, O, state_o,
-                        state_ml, stream);
+                        state_ml, nullptr, stream);
+}
+
+extern "C" int lf_sparse_attn_fwd(const void* Q, const void* K, const void* V, const lf_shape* s,
+                                  const int32_t* indices, int32_t list_len, float softmax_scale,
+                                  void* O, float* lse2, void* stream) {
+  if (!Q || !K || !V || !s || !indices || !O || !lse2) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, nullptr, &dm);
+  if (rc != LF_OK) return rc;
+  if (list_len < 1) return LF_ERR_BUDGET;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return LF_ERR_SHAPE;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
+      misaligned(indices, 4) || misaligned(lse2, 4))
+    return LF_ERR_ALIGN;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
+  return lf_launch_attn(Q, K, V, s, &dm, indices, list_len, list_len, scale, O, nullptr, nullptr, lse2,
+                        stream);
+}
+
+// Scratch of lf_sparse_attn_bwd: delta float32 [H][q_len], the transposed lists int32
+// [H][n_k][n_q] and their lengths int32 [H][n_k].
+static size_t attn_bwd_bytes(const lf_dims& dm, size_t* off_tlist, size_t* off_tcnt) {
+  const size_t rows = (size_t)dm.H * dm.f * dm.n;
+  const size_t o1 = align_up(rows * sizeof(float), 256);
+  const size_t o2 = o1 + align_up((size_t)dm.H * dm.n_k * dm.n_q * sizeof(int32_t), 256);
+  if (off_tlist) *off_tlist = o1;
+  if (off_tcnt) *off_tcnt = o2;
+  return o2 + align_up((size_t)dm.H * dm.n_k * sizeof(int32_t), 256);
+}
+
+extern "C" size_t lf_attn_bwd_workspace_bytes(const lf_shape* s) {
+  lf_dims dm;
+  if (lf_derive(s, nullptr, &dm) != LF_OK) return 0;
+  return attn_bwd_bytes(dm, nullptr, nullptr);
+}
+
+extern "C" int lf_sparse_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+                                  const void* dO, const float* lse2, const lf_shape* s,
+                                  const int32_t* indices, int32_t list_len, float softmax_scale,
+                                  void* dQ, void* dK, void* dV, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (!Q || !K || !V || !O || !dO || !lse2 || !s || !indices || !dQ || !dK || !dV) return LF_ERR_NULL;
+  lf_dims dm;
+  int rc = lf_derive(s, nullptr, &dm);
+  if (rc != LF_OK) return rc;
+  if (list_len < 1) return LF_ERR_BUDGET;
+  if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return LF_ERR_SHAPE;
+  size_t off_tlist = 0, off_tcnt = 0;
+  const size_t need = attn_bwd_bytes(dm, &off_tlist, &off_tcnt);
+  if (!workspace || workspace_bytes < need) return LF_ERR_WORKSPACE;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
+      misaligned(dO, 16) || misaligned(dQ, 16) || misaligned(dK, 16) || misaligned(dV, 16) ||
+      misaligned(indices, 4) || misaligned(lse2, 4) || misaligned(workspace, 256))
+    return LF_ERR_ALIGN;
+  const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
+  return lf_launch_attn_bwd(Q, K, V, O, dO, lse2, s, &dm, indices, list_len, scale, dQ, dK, dV,
+                            (float*)workspace, (int32_t*)((char*)workspace + off_tlist),
+                            (int32_t*)((char*)workspace + off_tcnt), stream);
 }
 
 extern "C" int lf_qk_norm_rope(const void* X, const float* g, const float* cos_table,

@@ -95,6 +95,14 @@ def load() -> C.CDLL:
     lib.lf_sparse_attn_split.argtypes = [vp, vp, vp, C.POINTER(lf_shape), C.POINTER(lf_budget), vp,
                                          C.c_float, vp, vp, C.c_size_t, vp]
     lib.lf_sparse_attn_split.restype = C.c_int
+    lib.lf_sparse_attn_fwd.argtypes = [vp, vp, vp, C.POINTER(lf_shape), vp, C.c_int32, C.c_float,
+                                       vp, vp, vp]
+    lib.lf_sparse_attn_fwd.restype = C.c_int
+    lib.lf_attn_bwd_workspace_bytes.argtypes = [C.POINTER(lf_shape)]
+    lib.lf_attn_bwd_workspace_bytes.restype = C.c_size_t
+    lib.lf_sparse_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(lf_shape), vp, C.c_int32,
+                                       C.c_float, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.lf_sparse_attn_bwd.restype = C.c_int
     lib.lf_qk_norm_rope.argtypes = [vp, vp, vp, vp, C.POINTER(lf_producer_shape), vp, vp]
     lib.lf_qk_norm_rope.restype = C.c_int
     lib.lf_kcache_bytes.argtypes = [C.POINTER(lf_shape), C.c_int32]
@@ -338,6 +346,75 @@ def lf_sparse_attn_split(Q, Kcache, Vcache, indices, frame_len: int, block: int,
     if rc != LF_OK:
         raise LfError(rc, "lf_sparse_attn_split")
     return O
+
+
+def _check_lists(indices, sh, frame_len):
+    import torch
+    if not indices.is_cuda or indices.dtype != torch.int32 or not indices.is_contiguous():
+        raise ValueError("indices must be a contiguous int32 GPU tensor [H, n_q, list_len]")
+    n_q = (sh.q_len // frame_len) * (-(-frame_len // sh.block)) if frame_len > 0 else -1
+    if indices.dim() != 3 or indices.shape[0] != sh.heads or indices.shape[1] != n_q:
+        raise ValueError("indices must be [H, n_q, list_len]")
+
+
+def lf_sparse_attn_fwd(Q, Kcache, Vcache, indices, frame_len: int, block: int,
+                       softmax_scale: float = 0.0, O=None, lse2=None, stream=None):
+    """Blockwise sparse attention that also leaves the rows' log-sum-exp (exp2 domain) for
+    lf_sparse_attn_bwd; returns (O, lse2)."""
+    import torch
+    _check_tensor(Q, "Q")
+    _check_tensor(Kcache, "Kcache")
+    _check_tensor(Vcache, "Vcache")
+    if O is None:
+        O = torch.empty_like(Q, memory_format=torch.contiguous_format)
+    _check_tensor(O, "O")
+    sh = make_shape(Q, Kcache, Vcache, O, frame_len=frame_len, block=block)
+    _check_lists(indices, sh, frame_len)
+    if lse2 is None:
+        lse2 = torch.empty((sh.heads, sh.q_len), dtype=torch.float32, device=Q.device)
+    if lse2.dtype != torch.float32 or not lse2.is_cuda or not lse2.is_contiguous() \
+            or tuple(lse2.shape) != (sh.heads, sh.q_len):
+        raise ValueError("lse2 must be a contiguous float32 GPU tensor [H, q_len]")
+    rc = load().lf_sparse_attn_fwd(Q.data_ptr(), Kcache.data_ptr(), Vcache.data_ptr(), C.byref(sh),
+                                   indices.data_ptr(), int(indices.shape[-1]), float(softmax_scale),
+                                   O.data_ptr(), lse2.data_ptr(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_sparse_attn_fwd")
+    return O, lse2
+
+
+def lf_attn_bwd_workspace_bytes(shape: lf_shape) -> int:
+    return int(load().lf_attn_bwd_workspace_bytes(C.byref(shape)))
+
+
+def lf_sparse_attn_bwd(Q, Kcache, Vcache, O, dO, lse2, indices, frame_len: int, block: int,
+                       softmax_scale: float = 0.0, workspace=None, stream=None):
+    """Gradients of the blockwise sparse attention; returns (dQ, dK, dV), bfloat16 with the
+    strides of Q, Kcache and Vcache.  ``indices`` ascending and duplicate-free per list."""
+    import torch
+    for t, name in ((Q, "Q"), (Kcache, "Kcache"), (Vcache, "Vcache"), (O, "O"), (dO, "dO")):
+        _check_tensor(t, name)
+    if tuple(dO.shape) != tuple(O.shape) or dO.stride() != O.stride():
+        raise ValueError("dO must have the shape and strides of O")
+    sh = make_shape(Q, Kcache, Vcache, O, frame_len=frame_len, block=block)
+    _check_lists(indices, sh, frame_len)
+    if lse2.dtype != torch.float32 or not lse2.is_cuda or not lse2.is_contiguous() \
+            or tuple(lse2.shape) != (sh.heads, sh.q_len):
+        raise ValueError("lse2 must be a contiguous float32 GPU tensor [H, q_len]")
+    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    dK = torch.empty_strided(Kcache.shape, Kcache.stride(), dtype=Q.dtype, device=Q.device)
+    dV = torch.empty_strided(Vcache.shape, Vcache.stride(), dtype=Q.dtype, device=Q.device)
+    if workspace is None:
+        workspace = torch.empty(max(lf_attn_bwd_workspace_bytes(sh), 256), dtype=torch.uint8,
+                                device=Q.device)
+    rc = load().lf_sparse_attn_bwd(Q.data_ptr(), Kcache.data_ptr(), Vcache.data_ptr(), O.data_ptr(),
+                                   dO.data_ptr(), lse2.data_ptr(), C.byref(sh), indices.data_ptr(),
+                                   int(indices.shape[-1]), float(softmax_scale), dQ.data_ptr(),
+                                   dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != LF_OK:
+        raise LfError(rc, "lf_sparse_attn_bwd")
+    return dQ, dK, dV
 
 
 def lf_qk_norm_rope(X, g, cos_table, sin_table, heads: int, Y, eps: float = 1e-6,

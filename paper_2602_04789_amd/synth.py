@@ -293,6 +293,14 @@ def small_ragged(seed: int = 11, heads: int = 3, head_dim: int = 128, frame_len:
 # Inputs of the Q/K producer (RMSNorm + rotary embedding)
 # ---------------------------------------------------------------------------
 
+def make_upstream_grad(w: Workload, seed: int = 5) -> np.ndarray:
+    """Upstream gradient dO of the attention output, bfloat16 bits [H, q_len, d]: independent
+    standard normal entries (what a loss hands back through an output projection has no
+    structure the backward pass could exploit)."""
+    rng = np.random.default_rng([seed, 91, w.chunk_idx, w.heads, w.head_dim])
+    return _round_bf16(rng.standard_normal((w.heads, w.q_len, w.head_dim), dtype=np.float32))
+
+
 def make_producer_inputs(tokens: int, heads: int, head_dim: int, seed: int,
                          grid_hw: Tuple[int, int] = (30, 52), x_pad: int = 0) -> Dict[str, np.ndarray]:
     """Token-major activations X [tokens, heads*head_dim + x_pad] (bfloat16 bits; what a

@@ -19,7 +19,12 @@ int lf_launch_kcache_update(const void*, const lf_shape*, const lf_dims*, int, i
 int lf_launch_select_cached(const void*, const void*, void*, int, const lf_shape*, const lf_budget*,
                             const lf_dims*, int32_t*, void*, void*) { ++g_launches; return LF_OK; }
 int lf_launch_attn(const void*, const void*, const void*, const lf_shape*, const lf_dims*, const int32_t*,
-                   int32_t, int32_t, float, void*, const float*, const float*, void*) { ++g_launches; return LF_OK; }
+                   int32_t, int32_t, float, void*, const float*, const float*, float*, void*) {
+  ++g_launches; return LF_OK;
+}
+int lf_launch_attn_bwd(const void*, const void*, const void*, const void*, const void*, const float*,
+                       const lf_shape*, const lf_dims*, const int32_t*, int32_t, float, void*, void*, void*,
+                       float*, int32_t*, int32_t*, void*) { ++g_launches; return LF_OK; }
 int lf_launch_attn_dense(const void*, const void*, const void*, const lf_shape*, const lf_dims*, int, int,
                          float, float*, float*, void*) { ++g_launches; return LF_OK; }
 int lf_launch_qk_norm_rope(const void*, const float*, const float*, const float*, const lf_producer_shape*,
@@ -86,8 +91,13 @@ int main() {
   EXPECT(lf_sparse_attn_split(P, P, P, &h, &b, (const int32_t*)P, 0.0f, P, P, aws, nullptr) == LF_OK);
   EXPECT(lf_kcache_update(P, &h, 0, 21, 21, P, kcb, nullptr) == LF_OK);
   EXPECT(lf_select_mask_cached(P, P, P, kcb, 21, &h, &b, (int32_t*)P, P, ws, nullptr) == LF_OK);
+  const size_t bws = lf_attn_bwd_workspace_bytes(&h);
+  EXPECT(bws > 0);
+  EXPECT(lf_sparse_attn_fwd(P, P, P, &h, (const int32_t*)P, 188, 0.0f, P, (float*)P, nullptr) == LF_OK);
+  EXPECT(lf_sparse_attn_bwd(P, P, P, P, P, (const float*)P, &h, (const int32_t*)P, 188, 0.0f, P, P, P, P, bws,
+                            nullptr) == LF_OK);
   const int accepted = g_launches;
-  EXPECT(accepted == 7);   // the split call launches two kernels
+  EXPECT(accepted == 9);   // the split call launches two kernels; the backward stub counts once
 
   EXPECT(lf_select_mask(nullptr, P, &h, &b, (int32_t*)P, P, ws, nullptr) == LF_ERR_NULL);
   EXPECT(lf_select_mask(P, P, &h, &b, (int32_t*)P, P, ws - 1, nullptr) == LF_ERR_WORKSPACE);
@@ -95,6 +105,11 @@ int main() {
   EXPECT(lf_sparse_attn(P, P, P, &h, (const int32_t*)P, 0, 0.0f, P, nullptr) == LF_ERR_BUDGET);
   EXPECT(lf_sparse_attn(P, P, P, &h, (const int32_t*)P, 188, -1.0f, P, nullptr) == LF_ERR_SHAPE);
   EXPECT(lf_sparse_attn_split(P, P, P, &h, &b, (const int32_t*)P, 0.0f, P, P, aws - 1, nullptr) == LF_ERR_WORKSPACE);
+  EXPECT(lf_sparse_attn_fwd(P, P, P, &h, (const int32_t*)P, 188, 0.0f, P, nullptr, nullptr) == LF_ERR_NULL);
+  EXPECT(lf_sparse_attn_bwd(P, P, P, P, P, (const float*)P, &h, (const int32_t*)P, 188, 0.0f, P, P, P, P, bws - 1,
+                            nullptr) == LF_ERR_WORKSPACE);
+  EXPECT(lf_sparse_attn_bwd(P, P, P, P, nullptr, (const float*)P, &h, (const int32_t*)P, 188, 0.0f, P, P, P, P,
+                            bws, nullptr) == LF_ERR_NULL);
   EXPECT(lf_kcache_update(P, &h, 5, 4, 21, P, kcb, nullptr) == LF_ERR_SHAPE);
   EXPECT(lf_kcache_update(P, &h, 0, 21, 21, P, kcb - 1, nullptr) == LF_ERR_WORKSPACE);
   EXPECT(lf_select_mask_cached(P, P, P, kcb, 20, &h, &b, (int32_t*)P, P, ws, nullptr) == LF_ERR_SHAPE);

@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol(lib):
     assert {"lf_chunk_budget", "lf_select_mask", "lf_sparse_attn", "lf_workspace_bytes",
             "lf_workspace_layout", "lf_strerror", "lf_version", "lf_kcache_bytes",
             "lf_kcache_update", "lf_select_mask_cached", "lf_sparse_attn_split",
-            "lf_attn_workspace_bytes", "lf_select_mask_static", "lf_init", "lf_qk_norm_rope"} <= names
+            "lf_attn_workspace_bytes", "lf_select_mask_static", "lf_init", "lf_qk_norm_rope",
+            "lf_sparse_attn_fwd", "lf_sparse_attn_bwd", "lf_attn_bwd_workspace_bytes"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert lf.lf_version() >= 100
@@ -235,6 +236,31 @@ def test_sparse_attn_split_argument_errors_enqueue_nothing(lib):
     _, s2, _ = _good()
     s2.head_dim = 96
     assert lf.lf_attn_workspace_bytes(s2) == 0 and call(s=s2) == -2
+
+
+def test_sparse_attn_training_pair_argument_errors_enqueue_nothing(lib):
+    w, sh, b = _good()
+    fwd = lambda Q=FAKE, K=FAKE, V=FAKE, s=sh, idx=FAKE, ll=188, sc=0.0, Out=FAKE, lse=FAKE: \
+        lib.lf_sparse_attn_fwd(Q, K, V, C.byref(s) if s is not None else None, idx, ll, sc, Out, lse, None)
+    assert fwd(Q=None) == -1 and fwd(lse=None) == -1 and fwd(Out=None) == -1 and fwd(s=None) == -1
+    assert fwd(ll=0) == -3 and fwd(sc=-1.0) == -2 and fwd(lse=FAKE + 2) == -5 and fwd(K=FAKE + 8) == -5
+    need = lf.lf_attn_bwd_workspace_bytes(sh)
+    nb = -(-w.frame_len // w.block)
+    n_q, n_k = w.frames_per_chunk * nb, w.frames * nb
+    assert need >= w.heads * (w.q_len * 4 + n_k * n_q * 4 + n_k * 4)
+    bwd = lambda Q=FAKE, K=FAKE, V=FAKE, Out=FAKE, dO=FAKE, lse=FAKE, s=sh, idx=FAKE, ll=188, sc=0.0, \
+        dQ=FAKE, dK=FAKE, dV=FAKE, ws=FAKE, nbytes=need: \
+        lib.lf_sparse_attn_bwd(Q, K, V, Out, dO, lse, C.byref(s) if s is not None else None, idx, ll, sc,
+                               dQ, dK, dV, ws, nbytes, None)
+    for kw in (dict(Q=None), dict(K=None), dict(V=None), dict(Out=None), dict(dO=None), dict(lse=None),
+               dict(s=None), dict(idx=None), dict(dQ=None), dict(dK=None), dict(dV=None)):
+        assert bwd(**kw) == -1, kw
+    assert bwd(ll=0) == -3 and bwd(sc=float("inf")) == -2
+    assert bwd(ws=None) == -6 and bwd(nbytes=need - 1) == -6 and bwd(ws=FAKE + 16) == -5
+    assert bwd(dO=FAKE + 8) == -5 and bwd(dK=FAKE + 4) == -5 and bwd(lse=FAKE + 1) == -5
+    _, s2, _ = _good()
+    s2.head_dim = 96
+    assert lf.lf_attn_bwd_workspace_bytes(s2) == 0 and bwd(s=s2) == -2 and fwd(s=s2) == -2
 
 
 def test_qk_norm_rope_argument_errors_enqueue_nothing(lib):
