@@ -8,20 +8,20 @@
 // p is rebuilt from the row's log-sum-exp, which the training forward call leaves (in the exp2
 // domain: lse2_x = log2 sum_y exp2(s_xy log2 e)), so no row maximum or sum is needed here.
 //
-// No atomics and a fixed summation order: two passes of one kernel template, each owning its
-// outputs.  Pass 1 is query-major (a workgroup owns a query block, walks its list of KV blocks,
-// keeps dQ in registers); pass 2 is key-major (a workgroup owns a KV block, walks the list of
-// query blocks that keep it -- the transposed lists, made by a small kernel -- and keeps dK and
-// dV in registers).  Both recompute the scores of a tile; in both the products are arranged as
-// in the forward kernel: the "score-like" products S' = A1 X^T and dP' = A2 Y^T take their A
+// No atomics and a fixed summation order: every launch owns its outputs.  The dQ launch is
+// query-major (a workgroup owns a query block, walks its list of KV blocks, keeps dQ in
+// registers); the dK and the dV launch are key-major (a workgroup owns a KV block and walks the
+// list of query blocks that keep it -- the transposed lists, made by a small kernel).  All three
+// are one kernel template and recompute the scores of a tile.  The products are arranged as in
+// the forward kernel: the "score-like" products S' = A1 X^T and dP' = A2 Y^T take their A
 // operand from a 32-row tile in LDS (row reads) and their B operand from registers that hold the
 // owner block, which leaves a lane with one owner column and 16 stream rows; P' and dS' are then
-// already in the B-operand layout of the accumulating products, whose A operand is the same tile
+// already in the B-operand layout of the accumulating product, whose A operand is the same tile
 // read through the transposing LDS read.
-//     pass 1: owner = query block (X = Q, Y = dO), stream = KV blocks (A1 = K, A2 = V),
-//             dQ^T += K^T dS'
-//     pass 2: owner = KV block (X = K, Y = V), stream = query blocks (A1 = Q, A2 = dO),
-//             dV^T += dO^T P',  dK^T += Q^T dS'
+//     dQ:      owner = query block (X = Q, Y = dO), stream = KV blocks (A1 = K, A2 = V),
+//              dQ^T += K^T dS'
+//     dK, dV:  owner = KV block (X = K, Y = V), stream = query blocks (A1 = Q, A2 = dO),
+//              dK^T += Q^T dS'   /   dV^T += dO^T P'  (no dP' needed)
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -39,16 +39,16 @@ constexpr int kThreads = 128;    // two wavefronts of 32 owner rows each
 constexpr int kPass = 256;       // list entries decoded per pass
 
 struct BwdArgs {
-  const uint16_t* X;     // owner-side operand of the scores (Q in pass 1, K in pass 2)
-  const uint16_t* Y;     // owner-side operand of dP (dO in pass 1, V in pass 2)
-  const uint16_t* A1;    // streamed operand of the scores (K in pass 1, Q in pass 2)
-  const uint16_t* A2;    // streamed operand of dP (V in pass 1, dO in pass 2)
-  uint16_t* out1;        // dQ (pass 1) or dK (pass 2): scale * sum of A1^T dS'
-  uint16_t* out2;        // dV (pass 2 only): sum of A2^T P'
-  const float* lse2;     // [H][q_len]
-  const float* delta;    // [H][q_len]
+  const uint16_t* X;     // owner-side operand of the scores (Q for dQ, K for dK and dV)
+  const uint16_t* Y;     // owner-side operand of dP (dO for dQ, V for dK)
+  const uint16_t* A1;    // streamed operand of the scores (K for dQ, Q for dK and dV)
+  const uint16_t* A2;    // streamed operand of dP (V for dQ, dO for dK and dV)
+  uint16_t* out1;        // dQ or dK: scale * sum of A1^T dS'
+  uint16_t* out2;        // dV: sum of A2^T P'
+  const float2* stats;   // (lse2, delta) per query row, [H][q_len]
   const int32_t* idx;    // lists: [H][owners][list_stride]
   const int32_t* cnt;    // entries per list, or null: list_len for all
+  const int32_t* order;  // owner handled by workgroup slot w, or null: slot w handles owner w
   int64_t x_tok, x_head, y_tok, y_head, a1_tok, a1_head, a2_tok, a2_head;
   int64_t o1_tok, o1_head, o2_tok, o2_head;
   int n, nb, owners, streams, list_len, list_stride, q_len;
@@ -65,12 +65,17 @@ union Frag {
 
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-// One swizzle for both tiles of a step: it has to serve row reads (16 bytes per lane, 32
-// consecutive rows) and the transposing reads (32 bytes from each of four consecutive rows per
-// group of 16 lanes); shifting each of eight consecutive rows by two 16-byte chunks does.
+// One swizzle for both tiles of a step: it has to serve row reads (16 bytes per lane, 16
+// consecutive rows at one logical chunk per quarter wavefront) and the transposing reads (32
+// bytes from each of four consecutive rows per group of 16 lanes).  Shifting each of eight
+// consecutive rows by two 16-byte chunks is what the forward kernel found best for the
+// transposing reads; flipping the lowest chunk bit for the second eight rows on top of that
+// makes the 16 rows of a row read land in 16 different chunks.
 template <int CH> __device__ __forceinline__ int swz(int row, int ch) {
-  return CH == 16 ? ch ^ ((row & 7) << 1) : ch ^ ((row & 1) << 2);
+  return CH == 16 ? ch ^ ((row & 7) << 1) ^ ((row >> 3) & 1) : ch ^ ((row & 1) << 2);
 }
+// The transposing read of rows 8..15 of a 16-row group sees the flipped bit: 8 elements aside.
+template <int CH> constexpr int kTrHiFlip = CH == 16 ? 8 : 0;
 
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
@@ -79,23 +84,31 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-// KVMAJOR = false: pass 1 (owner = query block); true: pass 2 (owner = KV block).
-template <int D, bool KVMAJOR>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, KVMAJOR ? 1 : 2)))
-void lf_attn_bwd_kernel(BwdArgs a) {
+// MODE 0: dQ (owner = query block).  MODE 1: dK, MODE 2: dV (owner = KV block).  dK and dV are
+// two launches: with both accumulator sets and both owner operands in registers a wavefront
+// needs more than the 256 registers that two wavefronts per SIMD leave each, and the fused
+// kernel at one wavefront per SIMD (software-pipelined, tiles triple-buffered) measured slower
+// than the two launches together although those compute the scores twice.
+template <int D, int MODE>
+__global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
+  constexpr bool KVMAJOR = MODE != 0;      // owner = KV block, stream = query blocks
+  constexpr bool NEED_DP = MODE != 2;      // dS' is needed (dQ, dK); dV takes P' only
   constexpr int CH = D / 8;
   constexpr int KS = D / 16;
   constexpr int MB = D / 32;
   constexpr int RPI = 64 / CH;
   constexpr int LPW = 32 / (RPI * 2);
   constexpr int TILE = 32 * CH;             // uint4 per 32-row tile
+  constexpr int NBUF = 2;
 
-  __shared__ uint4 buf[2][2 * TILE];        // [step parity][A1 tile | A2 tile]
+  __shared__ uint4 buf[NBUF][2 * TILE];     // [step mod NBUF][A1 tile | A2 tile]
   __shared__ int2 ent[kPass];               // (first token, token count) per list entry of a pass
-  __shared__ float2 st[2][32];              // pass 2: (lse2, delta) of the 32 streamed query rows
+  __shared__ float2 st[NBUF][2][32];        // key-major: (lse2, delta) of the 32 streamed query rows,
+                                            // one copy per wavefront
 
-  const int w = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
-  if (w >= a.total_wg) return;
+  const int slot = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  if (slot >= a.total_wg) return;
+  const int w = a.order ? a.order[slot] : slot;
   const int h = w / a.owners, r = w % a.owners;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -118,19 +131,17 @@ void lf_attn_bwd_kernel(BwdArgs a) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       xf[s].u = o_ok ? *reinterpret_cast<const uint4*>(xp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
-      yf[s].u = o_ok ? *reinterpret_cast<const uint4*>(yp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
+      yf[s].u = (o_ok && NEED_DP) ? *reinterpret_cast<const uint4*>(yp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
     }
   }
-  // pass 1: the query row of this lane; its log-sum-exp and delta (a row outside the block gets
+  // dQ: the query row of this lane; its log-sum-exp and delta (a row outside the block gets
   // +inf, which makes all its probabilities zero)
-  float my_lse = INFINITY, my_delta = 0.0f;
-  if (!KVMAJOR && o_ok) {
-    my_lse = a.lse2[(int64_t)h * a.q_len + otok0 + orow];
-    my_delta = a.delta[(int64_t)h * a.q_len + otok0 + orow];
-  }
+  float2 mine = make_float2(INFINITY, 0.0f);
+  if (!KVMAJOR && o_ok) mine = a.stats[(int64_t)h * a.q_len + otok0 + orow];
 
   const char* A1h = reinterpret_cast<const char*>(a.A1 + (int64_t)h * a.a1_head);
   const char* A2h = reinterpret_cast<const char*>(a.A2 + (int64_t)h * a.a2_head);
+  const char* STh = reinterpret_cast<const char*>(a.stats + (int64_t)h * a.q_len);
   const uint32_t a1_row_bytes = (uint32_t)(a.a1_tok * 2), a2_row_bytes = (uint32_t)(a.a2_tok * 2);
 
   // tile loads, global -> LDS (see the forward kernel): load i of wavefront `wave` fills rows
@@ -144,6 +155,7 @@ void lf_attn_bwd_kernel(BwdArgs a) {
     off1[i] = (uint32_t)row * a1_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
     off2[i] = (uint32_t)row * a2_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
   }
+  const uint32_t st_off = (uint32_t)lane * 4u;
   auto rsrc = [](const char* base, uint32_t row_bytes, int2 e) {
     int32x4 rs;
     const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)e.x * row_bytes;
@@ -169,11 +181,25 @@ void lf_attn_bwd_kernel(BwdArgs a) {
                    "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
                    :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs) : "memory", "m0");
   };
+  // the 32 (lse2, delta) pairs of a half tile are 256 contiguous bytes: one 4-byte load per lane
+  auto fetch_stats = [&](int2 e, float2* dst) __attribute__((always_inline)) {
+    const int32x4 rs = rsrc(STh, 8u, e);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(void, dst));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "buffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(lds0), "v"(st_off), "s"(rs) : "memory", "m0");
+  };
   // half tile t of the pass: list entry t/2, rows [32 (t&1), +32) of its block
-  auto half = [&](int t, int l1_local) {
-    const int2 e = ent[min(t >> 1, l1_local - 1)];
+  auto half = [&](int t, int n_local) {
+    const int2 e = ent[min(t >> 1, n_local - 1)];
     const int2 u = make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
     return (t & 1) ? make_int2(u.x + 32, max(u.y - 32, 0)) : make_int2(u.x, min(u.y, 32));
+  };
+  auto request = [&](int t, int n_local) __attribute__((always_inline)) {
+    const int2 e = half(t, n_local);
+    fetch(rsrc(A1h, a1_row_bytes, e), buf[t % NBUF], off1);
+    fetch(rsrc(A2h, a2_row_bytes, e), buf[t % NBUF] + TILE, off2);
+    if (KVMAJOR) fetch_stats(e, st[t % NBUF][wave]);
   };
 
   // LDS addresses of this lane's fragments (loop invariants): row reads of row ln, chunk 2s+kg
@@ -195,18 +221,71 @@ void lf_attn_bwd_kernel(BwdArgs a) {
   auto tfrag = [&](const uint4* tile, int u, int mb) __attribute__((always_inline)) {
     const uint16_t* p16 = reinterpret_cast<const uint16_t*>(tile);
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p16 + tbase[mb] + (16 * u) * CH * 8));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p16 + tbase[mb] + (16 * u + 8) * CH * 8));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        LDS_PTR(bf16x4, p16 + (tbase[mb] ^ kTrHiFlip<CH>) + (16 * u + 8) * CH * 8));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   };
 
-  f32x16 acc1[MB], acc2[MB];
+  f32x16 acc[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc1[mb][i] = acc2[mb][i] = 0.0f;
+    for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
   f32x16 zero16;
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
+
+  // S'[stream row, owner column] = A1 X^T and dP' = A2 Y^T of this wavefront's 32 x 32 tile
+  auto scores = [&](const uint4* tile, f32x16& sacc, f32x16& pacc) __attribute__((always_inline)) {
+    sacc = zero16;
+    pacc = zero16;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      Frag f1, f2;
+      f1.u = tile[raddr[s]];
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.v, xf[s].v, sacc, 0, 0, 0);
+      if (NEED_DP) {
+        f2.u = tile[TILE + raddr[s]];
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2.v, yf[s].v, pacc, 0, 0, 0);
+      }
+    }
+  };
+  // P' = exp2(s c - lse2), dS' = P' (dP' - delta), both packed to bfloat16 in the B-operand
+  // layout of the accumulating products; accumulator i is stream row 8 (i/4) + 4 kg + i%4
+  auto probs = [&](const f32x16& sacc, const f32x16& pacc, int cnt, const float2* strow, bf16x8 (&pf)[2],
+                   bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float4 sa, sb;     // key-major: (lse2, delta) of rows 8 g + 4 kg + {0,1} and {2,3}
+      if (KVMAJOR) {
+        sa = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg);
+        sb = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg + 2);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * g + e, row = 8 * g + 4 * kg + e;
+        float lse = mine.x, dl = mine.y;
+        if (KVMAJOR) {
+          lse = e == 0 ? sa.x : e == 1 ? sa.z : e == 2 ? sb.x : sb.z;
+          dl = e == 0 ? sa.y : e == 1 ? sa.w : e == 2 ? sb.y : sb.w;
+        }
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse));
+        if (row >= cnt) p = 0.0f;
+        pf[i >> 3][i & 7] = (__bf16)p;
+        dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - dl));
+      }
+    }
+  };
+  auto accumulate = [&](const uint4* tile, const bf16x8 (&pf)[2], const bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        // dQ, dK: A1^T dS';  dV: A2^T P'
+        const bf16x8 tf = tfrag(NEED_DP ? tile : tile + TILE, u, mb);
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, NEED_DP ? dsf[u] : pf[u], acc[mb], 0, 0, 0);
+      }
+  };
 
   for (int l0 = 0; l0 < n_ent; l0 += kPass) {
     const int l1 = min(n_ent, l0 + kPass);
@@ -222,101 +301,44 @@ void lf_attn_bwd_kernel(BwdArgs a) {
     __syncthreads();
 
     // step t uses buf[t & 1]; its tiles are requested one step ahead
-    float2 st_next = make_float2(INFINITY, 0.0f);
-    auto request = [&](int t) __attribute__((always_inline)) {
-      const int2 e = half(t, n_local);
-      fetch(rsrc(A1h, a1_row_bytes, e), buf[t & 1], off1);
-      fetch(rsrc(A2h, a2_row_bytes, e), buf[t & 1] + TILE, off2);
-      if (KVMAJOR && tid < 32) {
-        st_next = make_float2(INFINITY, 0.0f);
-        if (tid < e.y) {
-          st_next.x = a.lse2[(int64_t)h * a.q_len + e.x + tid];
-          st_next.y = a.delta[(int64_t)h * a.q_len + e.x + tid];
-        }
-      }
-    };
-    request(0);
+    request(0, n_local);
     for (int t = 0; t < steps; ++t) {
-      uint4* cur = buf[t & 1];
       const int cnt = half(t, n_local).y;
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-      if (KVMAJOR && tid < 32) st[t & 1][tid] = st_next;
       lds_barrier();
-      if (t + 1 < steps) request(t + 1);
-
-      // S'[stream row, owner column] and dP' of this wavefront's 32 x 32 tile
-      f32x16 sacc = zero16, pacc = zero16;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        Frag f1, f2;
-        f1.u = cur[raddr[s]];
-        f2.u = cur[TILE + raddr[s]];
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.v, xf[s].v, sacc, 0, 0, 0);
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2.v, yf[s].v, pacc, 0, 0, 0);
-      }
-      // P' = exp2(s c - lse2), dS' = P' (dP' - delta), both packed to bfloat16 in the B-operand
-      // layout of the accumulating products; accumulator i is stream row 8 (i/4) + 4 kg + i%4
+      if (t + 1 < steps) request(t + 1, n_local);
+      f32x16 sacc, pacc;
       bf16x8 pf[2], dsf[2];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int row = 8 * (i >> 2) + 4 * kg + (i & 3);
-        float lse = my_lse, dl = my_delta;
-        if (KVMAJOR) {
-          const float2 sd = st[t & 1][row];
-          lse = sd.x;
-          dl = sd.y;
-        }
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse));
-        if (row >= cnt) p = 0.0f;
-        pf[i >> 3][i & 7] = (__bf16)p;
-        dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - dl));
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const bf16x8 t1 = tfrag(cur, u, mb);
-          acc1[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t1, dsf[u], acc1[mb], 0, 0, 0);
-          if (KVMAJOR) {
-            const bf16x8 t2 = tfrag(cur + TILE, u, mb);
-            acc2[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t2, pf[u], acc2[mb], 0, 0, 0);
-          }
-        }
+      scores(buf[t & 1], sacc, pacc);
+      probs(sacc, pacc, cnt, st[t & 1][wave], pf, dsf);
+      accumulate(buf[t & 1], pf, dsf);
     }
   }
 
   // accumulator i of acc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of the owner row
   if (o_ok) {
-    uint16_t* p1 = a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok;
+    uint16_t* op = NEED_DP ? a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok
+                           : a.out2 + (int64_t)h * a.o2_head + (int64_t)(otok0 + orow) * a.o2_tok;
+    const float factor = NEED_DP ? a.scale : 1.0f;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         bf16x4 o4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc1[mb][4 * g + e] * a.scale);
-        *reinterpret_cast<bf16x4*>(p1 + 32 * mb + 8 * g + 4 * kg) = o4;
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[mb][4 * g + e] * factor);
+        *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
       }
-    if (KVMAJOR) {
-      uint16_t* p2 = a.out2 + (int64_t)h * a.o2_head + (int64_t)(otok0 + orow) * a.o2_tok;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 o4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o4[e] = (__bf16)acc2[mb][4 * g + e];
-          *reinterpret_cast<bf16x4*>(p2 + 32 * mb + 8 * g + 4 * kg) = o4;
-        }
-    }
   }
 }
 
-// delta_x = dO_x . O_x (float32), one 16-lane group per row.
+// delta_x = dO_x . O_x (float32), one group of d/8 lanes per row; written next to the row's
+// log-sum-exp, so that the attention kernels fetch both with one load.
 template <int D>
 __global__ __launch_bounds__(256) void lf_attn_delta_kernel(const uint16_t* __restrict__ O,
                                                             const uint16_t* __restrict__ dO,
-                                                            float* __restrict__ delta, int64_t o_tok,
+                                                            const float* __restrict__ lse2,
+                                                            float2* __restrict__ stats, int64_t o_tok,
                                                             int64_t o_head, int q_len, int rows) {
   constexpr int LPR = D / 8;                  // lanes per row
   const int gid = blockIdx.x * 256 + threadIdx.x;
@@ -335,37 +357,77 @@ __global__ __launch_bounds__(256) void lf_attn_delta_kernel(const uint16_t* __re
   }
 #pragma unroll
   for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o);
-  if (row < rows && ch == 0) delta[row] = s;
+  if (row < rows && ch == 0) stats[row] = make_float2(lse2[row], s);
 }
 
 // Transposed lists: for every (head, KV block c) the query blocks whose list holds c, ascending.
-// One thread per (head, c); every list is searched by bisection (lists are ascending).
-__global__ void lf_transpose_lists_kernel(const int32_t* __restrict__ idx, int32_t* __restrict__ tlist,
-                                          int32_t* __restrict__ tcnt, int heads, int n_q, int n_k,
-                                          int list_len) {
-  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+// One wavefront per (head, c): lane i looks c up in the list of query block r0 + i by bisection
+// (lists are ascending), and the hits of the 64 lanes are compacted in order through a ballot.
+__global__ __launch_bounds__(256) void lf_transpose_lists_kernel(const int32_t* __restrict__ idx,
+                                                                 int32_t* __restrict__ tlist,
+                                                                 int32_t* __restrict__ tcnt, int heads,
+                                                                 int n_q, int n_k, int list_len) {
+  const int gid = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (gid >= heads * n_k) return;
+  const int lane = threadIdx.x & 63;
   const int h = gid / n_k, c = gid % n_k;
   int32_t* out = tlist + (int64_t)gid * n_q;
   int cnt = 0;
-  for (int r = 0; r < n_q; ++r) {
-    const int32_t* l = idx + ((int64_t)h * n_q + r) * list_len;
-    int lo = 0, hi = list_len;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (l[mid] < c) lo = mid + 1; else hi = mid;
+  for (int r0 = 0; r0 < n_q; r0 += 64) {
+    const int r = r0 + lane;
+    bool hit = false;
+    if (r < n_q) {
+      const int32_t* l = idx + ((int64_t)h * n_q + r) * list_len;
+      int lo = 0, hi = list_len;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (l[mid] < c) lo = mid + 1; else hi = mid;
+      }
+      hit = lo < list_len && l[lo] == c;
     }
-    if (lo < list_len && l[lo] == c) out[cnt++] = r;
+    const uint64_t m = __ballot(hit);
+    if (hit) out[cnt + __popcll(m & ((1ull << lane) - 1))] = r;
+    cnt += __popcll(m);
   }
-  tcnt[gid] = cnt;
+  if (lane == 0) tcnt[gid] = cnt;
+}
+
+// Launch order of the key-major pass: its workgroups differ in work by the length of their
+// transposed list (a sink or current-chunk block is kept by every query block, a block of the
+// middle history by few), and workgroups are started in index order, so the long ones go first.
+// The workgroup indices are dealt to the eight XCDs in contiguous ranges (see the kernel); one
+// block per range sorts it by descending count with a counting sort.  The place of equal counts
+// among each other is left to the order the atomics happen to take: any permutation is valid,
+// and the gradients do not depend on which workgroup computes a block.
+constexpr int kOrderBins = 1024;
+__global__ __launch_bounds__(1024) void lf_order_kernel(const int32_t* __restrict__ tcnt,
+                                                        int32_t* __restrict__ order, int total,
+                                                        int per_xcd) {
+  __shared__ int bins[kOrderBins];
+  const int w0 = blockIdx.x * per_xcd, w1 = min(total, w0 + per_xcd);
+  for (int i = threadIdx.x; i < kOrderBins; i += 1024) bins[i] = 0;
+  __syncthreads();
+  for (int w = w0 + threadIdx.x; w < w1; w += 1024) atomicAdd(&bins[min(tcnt[w], kOrderBins - 1)], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int at = 0;
+    for (int b = kOrderBins - 1; b >= 0; --b) {
+      const int n = bins[b];
+      bins[b] = at;
+      at += n;
+    }
+  }
+  __syncthreads();
+  for (int w = w0 + threadIdx.x; w < w1; w += 1024)
+    order[w0 + atomicAdd(&bins[min(tcnt[w], kOrderBins - 1)], 1)] = w;
 }
 
 }  // namespace
 
 int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                        const float* lse2, const lf_shape* s, const lf_dims* dm, const int32_t* indices,
-                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* delta,
-                       int32_t* tlist, int32_t* tcnt, void* stream) {
+                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* stats,
+                       int32_t* tlist, int32_t* tcnt, int32_t* order, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int q_len = dm->f * dm->n;
   const int rows = dm->H * q_len;
@@ -374,26 +436,25 @@ int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* 
     const unsigned grid = (unsigned)((lanes + 255) / 256);
     const hipError_t rc = dm->d == 128
         ? lf_launch(lf_attn_delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const uint16_t*)O,
-                    (const uint16_t*)dO, delta, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows)
+                    (const uint16_t*)dO, lse2, (float2*)stats, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows)
         : lf_launch(lf_attn_delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const uint16_t*)O,
-                    (const uint16_t*)dO, delta, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows);
+                    (const uint16_t*)dO, lse2, (float2*)stats, (int64_t)s->o_stride_tok, (int64_t)s->o_stride_head, q_len, rows);
     if (rc != hipSuccess) return LF_ERR_HIP;
   }
   {
-    const unsigned grid = (unsigned)((dm->H * dm->n_k + 255) / 256);
+    const unsigned grid = (unsigned)((dm->H * dm->n_k + 3) / 4);
     if (lf_launch(lf_transpose_lists_kernel, dim3(grid), dim3(256), 0, st, indices, tlist, tcnt, dm->H,
                   dm->n_q, dm->n_k, (int)list_len) != hipSuccess)
       return LF_ERR_HIP;
   }
   BwdArgs a = {};
-  a.lse2 = lse2;
-  a.delta = delta;
+  a.stats = (const float2*)stats;
   a.n = dm->n;
   a.nb = dm->nb;
   a.q_len = q_len;
   a.c = scale * 1.4426950408889634f;
   a.scale = scale;
-  // pass 1: dQ
+  // dQ
   a.X = (const uint16_t*)Q;   a.x_tok = s->q_stride_tok;  a.x_head = s->q_stride_head;
   a.Y = (const uint16_t*)dO;  a.y_tok = s->o_stride_tok;  a.y_head = s->o_stride_head;
   a.A1 = (const uint16_t*)K;  a.a1_tok = s->k_stride_tok; a.a1_head = s->k_stride_head;
@@ -405,10 +466,10 @@ int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* 
   a.total_wg = dm->H * dm->n_q;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   hipError_t rc = dm->d == 128
-      ? lf_launch(lf_attn_bwd_kernel<128, false>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
-      : lf_launch(lf_attn_bwd_kernel<64, false>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
+      ? lf_launch(lf_attn_bwd_kernel<128, 0>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
+      : lf_launch(lf_attn_bwd_kernel<64, 0>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
   if (rc != hipSuccess) return LF_ERR_HIP;
-  // pass 2: dK, dV
+  // dK, then dV
   a.X = (const uint16_t*)K;   a.x_tok = s->k_stride_tok;  a.x_head = s->k_stride_head;
   a.Y = (const uint16_t*)V;   a.y_tok = s->v_stride_tok;  a.y_head = s->v_stride_head;
   a.A1 = (const uint16_t*)Q;  a.a1_tok = s->q_stride_tok; a.a1_head = s->q_stride_head;
@@ -419,8 +480,15 @@ int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* 
   a.owners = dm->n_k; a.streams = dm->n_q;
   a.total_wg = dm->H * dm->n_k;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
-  rc = dm->d == 128
-      ? lf_launch(lf_attn_bwd_kernel<128, true>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
-      : lf_launch(lf_attn_bwd_kernel<64, true>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
+  if (lf_launch(lf_order_kernel, dim3(8), dim3(1024), 0, st, (const int32_t*)tcnt, order, a.total_wg,
+                a.wg_per_xcd) != hipSuccess)
+    return LF_ERR_HIP;
+  a.order = order;
+  const dim3 grid2((unsigned)(a.wg_per_xcd * 8));
+  rc = dm->d == 128 ? lf_launch(lf_attn_bwd_kernel<128, 1>, grid2, dim3(kThreads), 0, st, a)
+                    : lf_launch(lf_attn_bwd_kernel<64, 1>, grid2, dim3(kThreads), 0, st, a);
+  if (rc != hipSuccess) return LF_ERR_HIP;
+  rc = dm->d == 128 ? lf_launch(lf_attn_bwd_kernel<128, 2>, grid2, dim3(kThreads), 0, st, a)
+                    : lf_launch(lf_attn_bwd_kernel<64, 2>, grid2, dim3(kThreads), 0, st, a);
   return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
 }

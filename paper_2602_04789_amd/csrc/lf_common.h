@@ -47,8 +47,8 @@ int lf_launch_attn(const void* Q, const void* K, const void* V, const lf_shape* 
                    void* stream);
 int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                        const float* lse2, const lf_shape* s, const lf_dims* dm, const int32_t* indices,
-                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* delta,
-                       int32_t* tlist, int32_t* tcnt, void* stream);
+                       int32_t list_len, float scale, void* dQ, void* dK, void* dV, float* stats,
+                       int32_t* tlist, int32_t* tcnt, int32_t* order, void* stream);
 int lf_launch_attn_dense(const void* Q, const void* K, const void* V, const lf_shape* s,
                          const lf_dims* dm, int kv0, int kv1, float scale, float* state_o,
                          float* state_ml, void* stream);

@@ -374,21 +374,23 @@ extern "C" int lf_sparse_attn_fwd(const void* Q, const void* K, const void* V, c
                         stream);
 }
 
-// Scratch of lf_sparse_attn_bwd: delta float32 [H][q_len], the transposed lists int32
-// [H][n_k][n_q] and their lengths int32 [H][n_k].
-static size_t attn_bwd_bytes(const lf_dims& dm, size_t* off_tlist, size_t* off_tcnt) {
+// Scratch of lf_sparse_attn_bwd: (lse2, delta) float32 [H][q_len][2], the transposed lists int32
+// [H][n_k][n_q], their lengths int32 [H][n_k] and the launch order int32 [H][n_k].
+static size_t attn_bwd_bytes(const lf_dims& dm, size_t* off_tlist, size_t* off_tcnt, size_t* off_order) {
   const size_t rows = (size_t)dm.H * dm.f * dm.n;
-  const size_t o1 = align_up(rows * sizeof(float), 256);
+  const size_t o1 = align_up(rows * 2 * sizeof(float), 256);
   const size_t o2 = o1 + align_up((size_t)dm.H * dm.n_k * dm.n_q * sizeof(int32_t), 256);
+  const size_t o3 = o2 + align_up((size_t)dm.H * dm.n_k * sizeof(int32_t), 256);
   if (off_tlist) *off_tlist = o1;
   if (off_tcnt) *off_tcnt = o2;
-  return o2 + align_up((size_t)dm.H * dm.n_k * sizeof(int32_t), 256);
+  if (off_order) *off_order = o3;
+  return o3 + align_up((size_t)dm.H * dm.n_k * sizeof(int32_t), 256);
 }
 
 extern "C" size_t lf_attn_bwd_workspace_bytes(const lf_shape* s) {
   lf_dims dm;
   if (lf_derive(s, nullptr, &dm) != LF_OK) return 0;
-  return attn_bwd_bytes(dm, nullptr, nullptr);
+  return attn_bwd_bytes(dm, nullptr, nullptr, nullptr);
 }
 
 extern "C" int lf_sparse_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
@@ -402,8 +404,8 @@ extern "C" int lf_sparse_attn_bwd(const void* Q, const void* K, const void* V, c
   if (rc != LF_OK) return rc;
   if (list_len < 1) return LF_ERR_BUDGET;
   if (!(softmax_scale >= 0.0f) || isinf(softmax_scale)) return LF_ERR_SHAPE;
-  size_t off_tlist = 0, off_tcnt = 0;
-  const size_t need = attn_bwd_bytes(dm, &off_tlist, &off_tcnt);
+  size_t off_tlist = 0, off_tcnt = 0, off_order = 0;
+  const size_t need = attn_bwd_bytes(dm, &off_tlist, &off_tcnt, &off_order);
   if (!workspace || workspace_bytes < need) return LF_ERR_WORKSPACE;
   if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
       misaligned(dO, 16) || misaligned(dQ, 16) || misaligned(dK, 16) || misaligned(dV, 16) ||
@@ -412,7 +414,8 @@ extern "C" int lf_sparse_attn_bwd(const void* Q, const void* K, const void* V, c
   const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)dm.d);
   return lf_launch_attn_bwd(Q, K, V, O, dO, lse2, s, &dm, indices, list_len, scale, dQ, dK, dV,
                             (float*)workspace, (int32_t*)((char*)workspace + off_tlist),
-                            (int32_t*)((char*)workspace + off_tcnt), stream);
+                            (int32_t*)((char*)workspace + off_tcnt),
+                            (int32_t*)((char*)workspace + off_order), stream);
 }
 
 extern "C" int lf_qk_norm_rope(const void* X, const float* g, const float* cos_table,

@@ -24,7 +24,7 @@ int lf_launch_attn(const void*, const void*, const void*, const lf_shape*, const
 }
 int lf_launch_attn_bwd(const void*, const void*, const void*, const void*, const void*, const float*,
                        const lf_shape*, const lf_dims*, const int32_t*, int32_t, float, void*, void*, void*,
-                       float*, int32_t*, int32_t*, void*) { ++g_launches; return LF_OK; }
+                       float*, int32_t*, int32_t*, int32_t*, void*) { ++g_launches; return LF_OK; }
 int lf_launch_attn_dense(const void*, const void*, const void*, const lf_shape*, const lf_dims*, int, int,
                          float, float*, float*, void*) { ++g_launches; return LF_OK; }
 int lf_launch_qk_norm_rope(const void*, const float*, const float*, const float*, const lf_producer_shape*,
