@@ -276,6 +276,36 @@ def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
     return res
 
 
+def time_training(torch, lf, synth, w, Q, K, V, idx, out, flops, n=20):
+    """Training pair (the paper finetunes with the sparse mask in place): the forward call that
+    also leaves the rows' log-sum-exp, and the backward call (delta, transposed lists, dQ, dK and
+    dV launches).  Algorithmic work of the backward: five products per kept tile (dV, dP, dQ, dK
+    and the recomputed scores), 2.5 x the forward's."""
+    dO = torch.from_numpy(synth.make_upstream_grad(w)).view(torch.bfloat16).cuda()
+    lse2 = torch.empty((w.heads, w.q_len), dtype=torch.float32, device="cuda")
+    sh = lf.make_shape(Q, K, V, out, frame_len=w.frame_len, block=w.block)
+    bws = torch.empty(lf.lf_attn_bwd_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
+    fwd = lambda: lf.lf_sparse_attn_fwd(Q, K, V, idx, w.frame_len, w.block, O=out, lse2=lse2)
+    bwd = lambda: lf.lf_sparse_attn_bwd(Q, K, V, out, dO, lse2, idx, w.frame_len, w.block, workspace=bws)
+    t_ms = []
+    for fn in (fwd, bwd):
+        for _ in range(3):
+            fn()
+        te = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
+        torch.cuda.synchronize()
+        for e in te:
+            e[0].record()
+            fn()
+            e[1].record()
+        torch.cuda.synchronize()
+        t_ms.append(float(np.mean([e[0].elapsed_time(e[1]) for e in te])))
+    tf = 2.5 * flops / (t_ms[1] * 1e-3) / 1e12
+    return {"what": "lf_sparse_attn_fwd (O and log-sum-exp) and lf_sparse_attn_bwd (dQ, dK, dV) on the same "
+                    "lists; backward work counted as 2.5 x the forward's kept flops",
+            "fwd_ms": t_ms[0], "bwd_ms": t_ms[1], "bwd_achieved": tf, "unit": "TFLOP/s",
+            "bwd_frac": tf / PEAK_BF16_TFLOPS}
+
+
 def run_rollout(args, torch, lf, synth):
     """One step = the 28 calls of a 7-chunk, 4-denoising-step rollout at 40 heads: the cache
     grows by one chunk per chunk index, the keep ratio follows the schedule, history K/V stay
@@ -352,6 +382,10 @@ def main():
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the per_config list (other benchmark configurations, the paper's own "
                          "operating points, one call per chunk of the 40-head rollout)")
+    ap.add_argument("--no-training", action="store_true",
+                    help="skip the timing of the training pair (forward with log-sum-exp, backward)")
+    ap.add_argument("--training-only", action="store_true",
+                    help="one selection, then only the training pair (for kernel traces of the backward)")
     ap.add_argument("--no-cached-select", action="store_true",
                     help="skip the pooled-key-cache variant of the selection (keeps profiles to the "
                          "four kernels of the main path)")
@@ -419,6 +453,13 @@ def main():
         lf.lf_select_mask(Q, K, w.frame_len, w.block, bb, indices=idx, workspace=ws)
         attend(bb)
 
+    if args.training_only:
+        step()
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": w.name,
+                          "training": time_training(torch, lf, synth, w, Q, K, V, idx, out,
+                                                    kept_flops(idx.cpu().numpy(), w), n=args.steps)}))
+        return
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -533,6 +574,8 @@ def main():
                                      "over the retrieved blocks", "ms": s_ms,
                              "achieved": flops / (s_ms * 1e-3) / 1e12, "unit": "TFLOP/s"}
         lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)   # `out` again holds the one-pass result
+    if not args.no_training:
+        res["training"] = time_training(torch, lf, synth, w, Q, K, V, idx, out, flops)
     if not args.no_cached_select:
         # Selection with the pooled-key cache: the history frames were pooled when their chunk was
         # generated (not timed: it happened in earlier calls of the rollout); a call pools only Q
