@@ -78,7 +78,7 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
         pobj = os.path.join(OBJ, f"lf_attn_probe_{tag}_hip.o")
         _run([hipcc, "-c", os.path.join(CSRC, "lf_attn.hip"), "-o", pobj, f"-DLF_PROBE_{tag.upper()}"] +
              COMMON + DEVICE + PER_FILE["lf_attn.hip"])
-        _run([hipcc, "-shared", "-o", probe_lib(tag)] + [o for o in objs if "lf_attn" not in o] + [pobj] +
+        _run([hipcc, "-shared", "-o", probe_lib(tag)] + [o for o in objs if os.path.basename(o) != "lf_attn_hip.o"] + [pobj] +
              ["--offload-arch=gfx950"])
     # the benchmark's micro-benchmarks: a library of their own, not linked into the product
     bobj = os.path.join(OBJ, "lf_bench_hip.o")

@@ -36,6 +36,16 @@ def test_library_exports_every_declared_symbol(lib):
     assert lf.lf_strerror(0) == "ok" and "NULL" in lf.lf_strerror(-1)
 
 
+def test_probe_and_benchmark_libraries_load(lib):
+    """The probe builds (product library with one redundant-work variant of the attention kernel)
+    and the micro-benchmark library resolve all their symbols."""
+    from paper_2602_04789_amd import build
+    for tag in build.PROBES:
+        probe = C.CDLL(build.probe_lib(tag))
+        assert hasattr(probe, "lf_sparse_attn") and hasattr(probe, "lf_sparse_attn_bwd")
+    assert hasattr(C.CDLL(build.BENCH_LIB), "lfb_stream_read")
+
+
 def test_struct_sizes_match_header(lib):
     # 12 int32 + 5 double; 8 int32 + double; 8 int32 + 8 int64
     assert C.sizeof(lf.lf_schedule) == 12 * 4 + 5 * 8
