@@ -281,11 +281,12 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   // itself, m_run starting at -1e30).  bfloat16 and float32 share their exponent range, so P,
   // the row sums and O stay finite far beyond that range, and O / l does not depend on m_run.
 #ifdef LF_PROBE_MFMA
-  f32x16 probe_acc[MB];
+  // one accumulator for all the extra products: 16 registers, so that the probe build still
+  // fits two wavefronts per SIMD without spilling (four accumulators made it spill, and the
+  // slowdown then measured the spills)
+  f32x16 probe_acc;
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) probe_acc[mb][i] = 0.0f;
+  for (int i = 0; i < 16; ++i) probe_acc[i] = 0.0f;
 #endif
   constexpr float kSumMax = 1.0e30f;
   float m_run = -1.0e30f, l_run = 0.0f;
@@ -484,7 +485,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
       for (int r2 = 0; r2 < 2; ++r2)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-          probe_acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0[mb], pf[r2], probe_acc[mb], 0, 0, 0);
+          probe_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0[mb], pf[r2], probe_acc, 0, 0, 0);
 #endif
 #ifdef LF_PROBE_EXP  // +16 exp2 (+100 %)
 #pragma unroll
@@ -516,9 +517,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   {
     float sd = 0.0f;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sd += probe_acc[mb][i];
+    for (int i = 0; i < 16; ++i) sd += probe_acc[i];
     if (sd == -123.0f) l_run += 1.0f;   // practically never true: keeps the extra products alive
   }
 #endif
