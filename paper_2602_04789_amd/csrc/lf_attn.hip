@@ -83,12 +83,17 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 
 // 16-byte chunk swizzles of the LDS tiles (row = token within the tile, ch = 8-channel chunk).
 // K is read row-wise, 16 bytes per lane, 16 consecutive rows at one logical chunk: XOR with
-// the row spreads them over all banks.  V is read with the transposing 8-byte LDS read, which
-// takes 32 bytes from each of four consecutive rows per group of 16 lanes; of the XOR
-// patterns measured, shifting each of eight consecutive rows by two chunks was the fastest.
+// the row spreads them over all banks.  V is read with the transposing 8-byte LDS read: half a
+// wavefront takes 64 contiguous bytes (four chunks) from each of four consecutive rows, and the
+// four rows must land in four different quarters of the 64 banks: for 256-byte rows the row's
+// two low bits go to the chunk's two high bits; for 128-byte rows two consecutive rows already
+// sit in different halves and the row's second bit picks the quarter.  With these the counter
+// of LDS bank-conflict cycles reads zero for the kernel (it was a third of the LDS-active
+// cycles with a shift of two chunks per row).  Both are unchanged by +8 and +16 rows, which the
+// address arithmetic of the transposing reads relies on.
 template <int CH> __device__ __forceinline__ int k_swz(int row, int ch) { return ch ^ (row & (CH - 1)); }
 template <int CH> __device__ __forceinline__ int v_swz(int row, int ch) {
-  return CH == 16 ? ch ^ ((row & 7) << 1) : ch ^ ((row & 1) << 2);
+  return CH == 16 ? ch ^ ((row & 3) << 2) : ch ^ (((row >> 1) & 1) << 2);
 }
 
 // Workgroup barrier that orders LDS accesses only; the global->LDS loads are waited for

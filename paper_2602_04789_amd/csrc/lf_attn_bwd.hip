@@ -65,17 +65,19 @@ union Frag {
 
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
-// One swizzle for both tiles of a step: it has to serve row reads (16 bytes per lane, 16
-// consecutive rows at one logical chunk per quarter wavefront) and the transposing reads (32
-// bytes from each of four consecutive rows per group of 16 lanes).  Shifting each of eight
-// consecutive rows by two 16-byte chunks is what the forward kernel found best for the
-// transposing reads; flipping the lowest chunk bit for the second eight rows on top of that
-// makes the 16 rows of a row read land in 16 different chunks.
+// One swizzle for both tiles of a step, since each is read both ways.  Row reads: 16 bytes per
+// lane, 16 consecutive rows at one logical chunk per quarter wavefront, which must land in 16
+// different chunks.  Transposing reads: half a wavefront takes four consecutive chunks from each
+// of four consecutive rows (4 k .. 4 k + 3), which must land in four different quarters of the
+// banks.  For 256-byte rows: the row's two low bits go to the chunk's two high bits (the four
+// rows of a transposing read differ there), the next two row bits to the chunk's two low bits
+// (constant within a transposing read, and together a bijection of the 16 rows of a row read).
 template <int CH> __device__ __forceinline__ int swz(int row, int ch) {
-  return CH == 16 ? ch ^ ((row & 7) << 1) ^ ((row >> 3) & 1) : ch ^ ((row & 1) << 2);
+  return CH == 16 ? ch ^ (((row & 3) << 2) | ((row >> 2) & 3)) : ch ^ ((row & 1) << 2);
 }
-// The transposing read of rows 8..15 of a 16-row group sees the flipped bit: 8 elements aside.
-template <int CH> constexpr int kTrHiFlip = CH == 16 ? 8 : 0;
+// The transposing read of rows 8..15 of a 16-row group sees row bit 3, i.e. chunk bit 1, flipped:
+// 16 elements aside.
+template <int CH> constexpr int kTrHiFlip = CH == 16 ? 16 : 0;
 
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
