@@ -219,7 +219,7 @@ def run_sensitivity(torch, lf, synth, workload):
                       "baseline_tflops": flops / (base * 1e-3) / 1e12}))
 
 
-def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
+def time_config(torch, lf, synth, w, steps, warmup, check_lists=True, train=True):
     """select / attention times of one workload (HIP events on the launch stream), its kept FLOPs,
     and whether every index list equals the oracle's."""
     from oracle import hsa_oracle as O
@@ -268,6 +268,10 @@ def time_config(torch, lf, synth, w, steps, warmup, check_lists=True):
            "select_frac_of_hbm_peak": sel_bytes / (sel_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS}
     if b.current_mandatory:
         res["attn_split_ms"] = float(np.mean(rounds[1]))
+    if train:
+        one_pass()
+        tr = time_training(torch, lf, synth, w, Q, K, V, idx, out, flops, n=max(3, steps // 2))
+        res["bwd_ms"], res["bwd_tflops"] = tr["bwd_ms"], tr["bwd_achieved"]
     if check_lists:
         ob = O.chunk_budget(w.chunk_idx, w.schedule)
         want = O.select_mask(synth.bf16_bits_to_f32(x["Q"]), synth.bf16_bits_to_f32(x["K"]),
@@ -630,10 +634,10 @@ def main():
                  if n != args.workload]
         for n in names:
             print(f"per_config: {n}", file=sys.stderr, flush=True)
-            per.append(time_config(torch, lf, synth, _workloads()[n](), 20, 5))
+            per.append(time_config(torch, lf, synth, _workloads()[n](), 20, 5, train=not args.no_training))
         for chunk in range(1, 8):
             print(f"per_config: rollout chunk {chunk} (40 heads)", file=sys.stderr, flush=True)
-            per.append(time_config(torch, lf, synth, synth.cfg_rollout(chunk, 0), 10, 3))
+            per.append(time_config(torch, lf, synth, synth.cfg_rollout(chunk, 0), 10, 3, train=not args.no_training))
         res["per_config"] = per
         ro = [p for p in per if p["workload"].startswith("rollout_")]
         # a 5-second video's 7 chunks x 4 denoising steps, one layer: each chunk's call four times

@@ -388,9 +388,10 @@ def lf_attn_bwd_workspace_bytes(shape: lf_shape) -> int:
 
 
 def lf_sparse_attn_bwd(Q, Kcache, Vcache, O, dO, lse2, indices, frame_len: int, block: int,
-                       softmax_scale: float = 0.0, workspace=None, stream=None):
+                       softmax_scale: float = 0.0, workspace=None, stream=None, grads=None):
     """Gradients of the blockwise sparse attention; returns (dQ, dK, dV), bfloat16 with the
-    strides of Q, Kcache and Vcache.  ``indices`` ascending and duplicate-free per list."""
+    strides of Q, Kcache and Vcache (``grads``: three such tensors to write into instead of new
+    ones).  ``indices`` ascending and duplicate-free per list."""
     import torch
     for t, name in ((Q, "Q"), (Kcache, "Kcache"), (Vcache, "Vcache"), (O, "O"), (dO, "dO")):
         _check_tensor(t, name)
@@ -401,9 +402,16 @@ def lf_sparse_attn_bwd(Q, Kcache, Vcache, O, dO, lse2, indices, frame_len: int, 
     if lse2.dtype != torch.float32 or not lse2.is_cuda or not lse2.is_contiguous() \
             or tuple(lse2.shape) != (sh.heads, sh.q_len):
         raise ValueError("lse2 must be a contiguous float32 GPU tensor [H, q_len]")
-    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    dK = torch.empty_strided(Kcache.shape, Kcache.stride(), dtype=Q.dtype, device=Q.device)
-    dV = torch.empty_strided(Vcache.shape, Vcache.stride(), dtype=Q.dtype, device=Q.device)
+    if grads is None:
+        dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        dK = torch.empty_strided(Kcache.shape, Kcache.stride(), dtype=Q.dtype, device=Q.device)
+        dV = torch.empty_strided(Vcache.shape, Vcache.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        dQ, dK, dV = grads
+        for g, t, name in ((dQ, Q, "dQ"), (dK, Kcache, "dK"), (dV, Vcache, "dV")):
+            _check_tensor(g, name)
+            if tuple(g.shape) != tuple(t.shape) or g.stride() != t.stride():
+                raise ValueError(f"{name} must have the shape and strides of its input")
     if workspace is None:
         workspace = torch.empty(max(lf_attn_bwd_workspace_bytes(sh), 256), dtype=torch.uint8,
                                 device=Q.device)

@@ -215,3 +215,54 @@ def test_backward_is_reproducible(gpu):
     torch.cuda.synchronize()
     for s, t in zip(a, b):
         assert torch.equal(s, t)
+
+
+def test_training_step_replays_from_a_captured_graph(gpu):
+    """Selection, training forward and backward captured once into a HIP graph (the library
+    allocates, clears and synchronises nothing) and replayed on new inputs written into the same
+    buffers, with eager work and synchronisations between the replays; every replay must equal
+    the eager result bit for bit."""
+    torch, lf = gpu
+    w = synth.small_ragged(chunk_idx=4)
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    xs = []
+    for s in (11, 12, 13):
+        ws_ = synth.small_ragged(chunk_idx=4, seed=s)
+        x = synth.make_inputs(ws_)
+        x["dO"] = synth.make_upstream_grad(ws_, seed=s)
+        xs.append(x)
+    Q, K, V, dO = (_dev(torch, xs[0][k]).clone() for k in ("Q", "K", "V", "dO"))
+    sh = lf.make_shape(Q, K, V, Q, frame_len=w.frame_len, block=w.block)
+    ws = torch.empty(lf.lf_workspace_bytes(sh, b), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(lf.lf_attn_bwd_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
+    nq = w.frames_per_chunk * w.blocks_per_frame
+    idx = torch.empty((w.heads, nq, b.list_len), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(Q)
+    lse2 = torch.empty((w.heads, w.q_len), dtype=torch.float32, device="cuda")
+    grads = (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+
+    def step():
+        lf.lf_select_mask(Q, K, w.frame_len, w.block, b, indices=idx, workspace=ws)
+        lf.lf_sparse_attn_fwd(Q, K, V, idx, w.frame_len, w.block, O=out, lse2=lse2)
+        lf.lf_sparse_attn_bwd(Q, K, V, out, dO, lse2, idx, w.frame_len, w.block, workspace=bws, grads=grads)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for x in xs[1:] + xs[:1] + xs[1:2]:
+        for t, k in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+            t.copy_(_dev(torch, x[k]))
+        for t in grads:
+            t.fill_(7.0)
+        bws.fill_(255)
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in grads]
+        want_idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+        want_out, want_lse = lf.lf_sparse_attn_fwd(Q, K, V, want_idx, w.frame_len, w.block)
+        want = lf.lf_sparse_attn_bwd(Q, K, V, want_out, dO, want_lse, want_idx, w.frame_len, w.block)
+        torch.cuda.synchronize()
+        for a, e in zip(got, want):
+            assert torch.equal(a.view(torch.int16), e.view(torch.int16))
