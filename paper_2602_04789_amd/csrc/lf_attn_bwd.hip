@@ -237,19 +237,35 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
-  // S'[stream row, owner column] = A1 X^T and dP' = A2 Y^T of this wavefront's 32 x 32 tile
+  // S'[stream row, owner column] = A1 X^T and dP' = A2 Y^T of this wavefront's 32 x 32 tile.
+  // The fragment reads are kept KS/2 k-steps ahead of the products that use them (the compiler,
+  // left alone, issues each read right before its product and waits for it); the scheduling
+  // barriers pin that order.
   auto scores = [&](const uint4* tile, f32x16& sacc, f32x16& pacc) __attribute__((always_inline)) {
+    constexpr int HB = KS / 2;
+    Frag f1[HB], f2[HB];
     sacc = zero16;
     pacc = zero16;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      Frag f1, f2;
-      f1.u = tile[raddr[s]];
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.v, xf[s].v, sacc, 0, 0, 0);
+    for (int s = 0; s < HB; ++s) {
+      f1[s].u = tile[raddr[s]];
+      if (NEED_DP) f2[s].u = tile[TILE + raddr[s]];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < HB; ++s) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[s].v, xf[s].v, sacc, 0, 0, 0);
+      f1[s].u = tile[raddr[HB + s]];
       if (NEED_DP) {
-        f2.u = tile[TILE + raddr[s]];
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2.v, yf[s].v, pacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[s].v, pacc, 0, 0, 0);
+        f2[s].u = tile[TILE + raddr[HB + s]];
       }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int s = 0; s < HB; ++s) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[s].v, xf[HB + s].v, sacc, 0, 0, 0);
+      if (NEED_DP) pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[HB + s].v, pacc, 0, 0, 0);
     }
   };
   // P' = exp2(s c - lse2), dS' = P' (dP' - delta), both packed to bfloat16 in the B-operand
@@ -278,15 +294,26 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
       }
     }
   };
-  auto accumulate = [&](const uint4* tile, const bf16x8 (&pf)[2], const bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+  // dQ, dK: acc += A1^T dS';  dV: acc += A2^T P'.  The transposed fragments of the first 16
+  // stream rows are requested by `first_half` before the exp2 work, which covers their latency;
+  // those of the second 16 rows are requested between the products of the first.
+  auto first_half = [&](const uint4* tile, bf16x8 (&tf)[MB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int mb = 0; mb < MB; ++mb) tf[mb] = tfrag(NEED_DP ? tile : tile + TILE, 0, mb);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto accumulate = [&](const uint4* tile, bf16x8 (&tf)[MB], const bf16x8 (&pf)[2],
+                        const bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        // dQ, dK: A1^T dS';  dV: A2^T P'
-        const bf16x8 tf = tfrag(NEED_DP ? tile : tile + TILE, u, mb);
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, NEED_DP ? dsf[u] : pf[u], acc[mb], 0, 0, 0);
-      }
+    for (int mb = 0; mb < MB; ++mb) {
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], NEED_DP ? dsf[0] : pf[0], acc[mb], 0, 0, 0);
+      tf[mb] = tfrag(NEED_DP ? tile : tile + TILE, 1, mb);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], NEED_DP ? dsf[1] : pf[1], acc[mb], 0, 0, 0);
   };
 
   for (int l0 = 0; l0 < n_ent; l0 += kPass) {
@@ -311,9 +338,15 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
       if (t + 1 < steps) request(t + 1, n_local);
       f32x16 sacc, pacc;
       bf16x8 pf[2], dsf[2];
+      bf16x8 tf[MB];
       scores(buf[t & 1], sacc, pacc);
+      first_half(buf[t & 1], tf);
       probs(sacc, pacc, cnt, st[t & 1][wave], pf, dsf);
-      accumulate(buf[t & 1], pf, dsf);
+      // the accumulating products run at low priority, scores and exp2 at high priority: with
+      // two wavefronts per SIMD this helps to keep them in different parts of the step
+      __builtin_amdgcn_s_setprio(0);
+      accumulate(buf[t & 1], tf, pf, dsf);
+      __builtin_amdgcn_s_setprio(3);
     }
   }
 
