@@ -444,13 +444,20 @@ __global__ __launch_bounds__(1024) void lf_order_kernel(const int32_t* __restric
   __syncthreads();
   for (int w = w0 + threadIdx.x; w < w1; w += 1024) atomicAdd(&bins[min(tcnt[w], kOrderBins - 1)], 1);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int at = 0;
-    for (int b = kOrderBins - 1; b >= 0; --b) {
-      const int n = bins[b];
-      bins[b] = at;
-      at += n;
+  // bins[b] <- number of workgroups in bins above b (where bin b starts in the descending order):
+  // an inclusive scan over the reversed bins by doubling, minus the bin's own count
+  {
+    const int b = kOrderBins - 1 - threadIdx.x;   // thread i scans position i of the reversed bins
+    const int own = bins[b];
+    int run = own;
+    for (int d = 1; d < kOrderBins; d <<= 1) {
+      const int other = (int)threadIdx.x >= d ? bins[b + d] : 0;
+      __syncthreads();
+      run += other;
+      bins[b] = run;
+      __syncthreads();
     }
+    bins[b] = run - own;
   }
   __syncthreads();
   for (int w = w0 + threadIdx.x; w < w1; w += 1024)
