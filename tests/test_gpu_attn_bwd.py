@@ -72,6 +72,10 @@ SMALL = {
     "short_frame": lambda: synth.small_ragged(frame_len=40, chunk_idx=5, heads=2, k_frames=1),
     "tail_31": lambda: synth.small_ragged(frame_len=95, chunk_idx=3, heads=2),
     "tail_33_d64": lambda: synth.small_ragged(frame_len=97, chunk_idx=3, heads=2, head_dim=64),
+    # 260 one-block frames per chunk: lists of 266 entries and transposed lists of 260, both past
+    # the 256 entries the kernels decode per pass
+    "many_query_blocks": lambda: synth.small_ragged(frame_len=64, chunk_idx=2, frames_per_chunk=260, heads=1,
+                                                    head_dim=64, k_frames=3, n_sink=1, n_win=2),
 }
 
 
