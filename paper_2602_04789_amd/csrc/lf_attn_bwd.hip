@@ -10,18 +10,18 @@
 //
 // No atomics and a fixed summation order: every launch owns its outputs.  The dQ launch is
 // query-major (a workgroup owns a query block, walks its list of KV blocks, keeps dQ in
-// registers); the dK and the dV launch are key-major (a workgroup owns a KV block and walks the
-// list of query blocks that keep it -- the transposed lists, made by a small kernel).  All three
-// are one kernel template and recompute the scores of a tile.  The products are arranged as in
-// the forward kernel: the "score-like" products S' = A1 X^T and dP' = A2 Y^T take their A
-// operand from a 32-row tile in LDS (row reads) and their B operand from registers that hold the
-// owner block, which leaves a lane with one owner column and 16 stream rows; P' and dS' are then
+// registers); the dK/dV launch is key-major (a workgroup owns a KV block and walks the list of
+// query blocks that keep it -- the transposed lists, made by a small kernel -- and keeps dK and dV
+// in registers).  Both recompute the scores of a tile.  The products are arranged as in the
+// forward kernel: the "score-like" products S' = A1 X^T and dP' = A2 Y^T take their A operand
+// from a 32-row tile in LDS (row reads) and their B operand from registers that hold the owner
+// block, which leaves a lane with one owner column and 16 stream rows; P' and dS' are then
 // already in the B-operand layout of the accumulating product, whose A operand is the same tile
 // read through the transposing LDS read.
 //     dQ:      owner = query block (X = Q, Y = dO), stream = KV blocks (A1 = K, A2 = V),
 //              dQ^T += K^T dS'
 //     dK, dV:  owner = KV block (X = K, Y = V), stream = query blocks (A1 = Q, A2 = dO),
-//              dK^T += Q^T dS'   /   dV^T += dO^T P'  (no dP' needed)
+//              dK^T += Q^T dS'  and  dV^T += dO^T P', by two kinds of wavefront that share P'
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -47,8 +47,8 @@ struct BwdArgs {
   uint16_t* out2;        // dV: sum of A2^T P'
   const float2* stats;   // (lse2, delta) per query row, [H][q_len]
   const int32_t* idx;    // lists: [H][owners][list_stride]
-  const int32_t* cnt;    // entries per list, or null: list_len for all
-  const int32_t* order;  // owner handled by workgroup slot w, or null: slot w handles owner w
+  const int32_t* cnt;    // key-major: entries per transposed list
+  const int32_t* order;  // key-major: owner handled by workgroup slot w
   int64_t x_tok, x_head, y_tok, y_head, a1_tok, a1_head, a2_tok, a2_head;
   int64_t o1_tok, o1_head, o2_tok, o2_head;
   int n, nb, owners, streams, list_len, list_stride, q_len;
@@ -86,15 +86,10 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-// MODE 0: dQ (owner = query block).  MODE 1: dK, MODE 2: dV (owner = KV block).  dK and dV are
-// two launches: with both accumulator sets and both owner operands in registers a wavefront
-// needs more than the 256 registers that two wavefronts per SIMD leave each, and the fused
-// kernel at one wavefront per SIMD (software-pipelined, tiles triple-buffered) measured slower
-// than the two launches together although those compute the scores twice.
-template <int D, int MODE>
-__global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
-  constexpr bool KVMAJOR = MODE != 0;      // owner = KV block, stream = query blocks
-  constexpr bool NEED_DP = MODE != 2;      // dS' is needed (dQ, dK); dV takes P' only
+// dQ: a workgroup of two wavefronts owns a query block (wavefront rh its rows [32 rh, +32)) and
+// walks the block's list of KV blocks in half tiles of 32 KV rows.
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_q_kernel(BwdArgs a) {
   constexpr int CH = D / 8;
   constexpr int KS = D / 16;
   constexpr int MB = D / 32;
@@ -105,12 +100,9 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
 
   __shared__ uint4 buf[NBUF][2 * TILE];     // [step mod NBUF][A1 tile | A2 tile]
   __shared__ int2 ent[kPass];               // (first token, token count) per list entry of a pass
-  __shared__ float2 st[NBUF][2][32];        // key-major: (lse2, delta) of the 32 streamed query rows,
-                                            // one copy per wavefront
 
-  const int slot = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
-  if (slot >= a.total_wg) return;
-  const int w = a.order ? a.order[slot] : slot;
+  const int w = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  if (w >= a.total_wg) return;
   const int h = w / a.owners, r = w % a.owners;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,7 +115,7 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
   const bool o_ok = orow < o_cnt;
 
   const int32_t* list = a.idx + ((int64_t)h * a.owners + r) * a.list_stride;
-  const int n_ent = a.cnt ? a.cnt[(int64_t)h * a.owners + r] : a.list_len;
+  const int n_ent = a.list_len;
 
   // B operands: lane (column ln, k-group kg) holds 8 consecutive channels of its owner row
   Frag xf[KS], yf[KS];
@@ -133,17 +125,16 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       xf[s].u = o_ok ? *reinterpret_cast<const uint4*>(xp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
-      yf[s].u = (o_ok && NEED_DP) ? *reinterpret_cast<const uint4*>(yp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
+      yf[s].u = o_ok ? *reinterpret_cast<const uint4*>(yp + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
     }
   }
   // dQ: the query row of this lane; its log-sum-exp and delta (a row outside the block gets
   // +inf, which makes all its probabilities zero)
   float2 mine = make_float2(INFINITY, 0.0f);
-  if (!KVMAJOR && o_ok) mine = a.stats[(int64_t)h * a.q_len + otok0 + orow];
+  if (o_ok) mine = a.stats[(int64_t)h * a.q_len + otok0 + orow];
 
   const char* A1h = reinterpret_cast<const char*>(a.A1 + (int64_t)h * a.a1_head);
   const char* A2h = reinterpret_cast<const char*>(a.A2 + (int64_t)h * a.a2_head);
-  const char* STh = reinterpret_cast<const char*>(a.stats + (int64_t)h * a.q_len);
   const uint32_t a1_row_bytes = (uint32_t)(a.a1_tok * 2), a2_row_bytes = (uint32_t)(a.a2_tok * 2);
 
   // tile loads, global -> LDS (see the forward kernel): load i of wavefront `wave` fills rows
@@ -157,7 +148,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
     off1[i] = (uint32_t)row * a1_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
     off2[i] = (uint32_t)row * a2_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
   }
-  const uint32_t st_off = (uint32_t)lane * 4u;
   auto rsrc = [](const char* base, uint32_t row_bytes, int2 e) {
     int32x4 rs;
     const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)e.x * row_bytes;
@@ -183,14 +173,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
                    "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
                    :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs) : "memory", "m0");
   };
-  // the 32 (lse2, delta) pairs of a half tile are 256 contiguous bytes: one 4-byte load per lane
-  auto fetch_stats = [&](int2 e, float2* dst) __attribute__((always_inline)) {
-    const int32x4 rs = rsrc(STh, 8u, e);
-    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(void, dst));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
-                 "buffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(lds0), "v"(st_off), "s"(rs) : "memory", "m0");
-  };
   // half tile t of the pass: list entry t/2, rows [32 (t&1), +32) of its block
   auto half = [&](int t, int n_local) {
     const int2 e = ent[min(t >> 1, n_local - 1)];
@@ -201,7 +183,6 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
     const int2 e = half(t, n_local);
     fetch(rsrc(A1h, a1_row_bytes, e), buf[t % NBUF], off1);
     fetch(rsrc(A2h, a2_row_bytes, e), buf[t % NBUF] + TILE, off2);
-    if (KVMAJOR) fetch_stats(e, st[t % NBUF][wave]);
   };
 
   // LDS addresses of this lane's fragments (loop invariants): row reads of row ln, chunk 2s+kg
@@ -249,71 +230,53 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
 #pragma unroll
     for (int s = 0; s < HB; ++s) {
       f1[s].u = tile[raddr[s]];
-      if (NEED_DP) f2[s].u = tile[TILE + raddr[s]];
+      f2[s].u = tile[TILE + raddr[s]];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s = 0; s < HB; ++s) {
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[s].v, xf[s].v, sacc, 0, 0, 0);
       f1[s].u = tile[raddr[HB + s]];
-      if (NEED_DP) {
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[s].v, pacc, 0, 0, 0);
-        f2[s].u = tile[TILE + raddr[HB + s]];
-      }
+      pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[s].v, pacc, 0, 0, 0);
+      f2[s].u = tile[TILE + raddr[HB + s]];
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int s = 0; s < HB; ++s) {
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[s].v, xf[HB + s].v, sacc, 0, 0, 0);
-      if (NEED_DP) pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[HB + s].v, pacc, 0, 0, 0);
+      pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[s].v, yf[HB + s].v, pacc, 0, 0, 0);
     }
   };
-  // P' = exp2(s c - lse2), dS' = P' (dP' - delta), both packed to bfloat16 in the B-operand
-  // layout of the accumulating products; accumulator i is stream row 8 (i/4) + 4 kg + i%4
-  auto probs = [&](const f32x16& sacc, const f32x16& pacc, int cnt, const float2* strow, bf16x8 (&pf)[2],
-                   bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+  // P' = exp2(s c - lse2), dS' = P' (dP' - delta), packed to bfloat16 in the B-operand layout of
+  // the accumulating product; accumulator i is stream row 8 (i/4) + 4 kg + i%4
+  auto probs = [&](const f32x16& sacc, const f32x16& pacc, int cnt, bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float4 sa, sb;     // key-major: (lse2, delta) of rows 8 g + 4 kg + {0,1} and {2,3}
-      if (KVMAJOR) {
-        sa = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg);
-        sb = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg + 2);
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int i = 4 * g + e, row = 8 * g + 4 * kg + e;
-        float lse = mine.x, dl = mine.y;
-        if (KVMAJOR) {
-          lse = e == 0 ? sa.x : e == 1 ? sa.z : e == 2 ? sb.x : sb.z;
-          dl = e == 0 ? sa.y : e == 1 ? sa.w : e == 2 ? sb.y : sb.w;
-        }
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse));
-        if (row >= cnt) p = 0.0f;
-        pf[i >> 3][i & 7] = (__bf16)p;
-        dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - dl));
-      }
+    for (int i = 0; i < 16; ++i) {
+      const int row = 8 * (i >> 2) + 4 * kg + (i & 3);
+      float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -mine.x));
+      if (row >= cnt) p = 0.0f;
+      dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - mine.y));
     }
   };
-  // dQ, dK: acc += A1^T dS';  dV: acc += A2^T P'.  The transposed fragments of the first 16
+  // acc += K^T dS'.  The transposed fragments of the first 16
   // stream rows are requested by `first_half` before the exp2 work, which covers their latency;
   // those of the second 16 rows are requested between the products of the first.
   auto first_half = [&](const uint4* tile, bf16x8 (&tf)[MB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) tf[mb] = tfrag(NEED_DP ? tile : tile + TILE, 0, mb);
+    for (int mb = 0; mb < MB; ++mb) tf[mb] = tfrag(tile, 0, mb);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto accumulate = [&](const uint4* tile, bf16x8 (&tf)[MB], const bf16x8 (&pf)[2],
-                        const bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+  auto accumulate = [&](const uint4* tile, bf16x8 (&tf)[MB], const bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], NEED_DP ? dsf[0] : pf[0], acc[mb], 0, 0, 0);
-      tf[mb] = tfrag(NEED_DP ? tile : tile + TILE, 1, mb);
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], dsf[0], acc[mb], 0, 0, 0);
+      tf[mb] = tfrag(tile, 1, mb);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
-      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], NEED_DP ? dsf[1] : pf[1], acc[mb], 0, 0, 0);
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], dsf[1], acc[mb], 0, 0, 0);
   };
 
   for (int l0 = 0; l0 < n_ent; l0 += kPass) {
@@ -337,24 +300,302 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_kernel(BwdArgs a) {
       lds_barrier();
       if (t + 1 < steps) request(t + 1, n_local);
       f32x16 sacc, pacc;
-      bf16x8 pf[2], dsf[2];
+      bf16x8 dsf[2];
       bf16x8 tf[MB];
       scores(buf[t & 1], sacc, pacc);
       first_half(buf[t & 1], tf);
-      probs(sacc, pacc, cnt, st[t & 1][wave], pf, dsf);
+      probs(sacc, pacc, cnt, dsf);
       // the accumulating products run at low priority, scores and exp2 at high priority: with
       // two wavefronts per SIMD this helps to keep them in different parts of the step
       __builtin_amdgcn_s_setprio(0);
-      accumulate(buf[t & 1], tf, pf, dsf);
+      accumulate(buf[t & 1], tf, dsf);
       __builtin_amdgcn_s_setprio(3);
     }
   }
 
   // accumulator i of acc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of the owner row
   if (o_ok) {
-    uint16_t* op = NEED_DP ? a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok
-                           : a.out2 + (int64_t)h * a.o2_head + (int64_t)(otok0 + orow) * a.o2_tok;
-    const float factor = NEED_DP ? a.scale : 1.0f;
+    uint16_t* op = a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok;
+    const float factor = a.scale;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[mb][4 * g + e] * factor);
+        *reinterpret_cast<bf16x4*>(op + 32 * mb + 8 * g + 4 * kg) = o4;
+      }
+  }
+}
+
+// dK and dV in one launch without computing the scores twice: a workgroup of four wavefronts
+// owns one KV block and walks the query blocks that keep it in half tiles of 32 query rows.
+// Wavefront i = (rh, role): rh = owner row half; role 0 computes S' = Q K^T, P' and
+// dV^T += dO^T P'; role 1 computes dP' = dO V^T, dS' = P' (dP' - delta) and dK^T += Q^T dS'.
+// P' goes from the role-0 wavefront to its role-1 partner (same rh: the same lanes hold the same
+// elements) through LDS, and the partner uses it one step later, so the one barrier per step is
+// enough; a tile therefore lives for two steps and the stage is triple-buffered.  Each wavefront
+// keeps one owner operand and one accumulator set, which fits two wavefronts per SIMD (two
+// workgroups per CU, not in step with each other).
+constexpr int kKvThreads = 256;
+template <int D>
+__global__ __launch_bounds__(kKvThreads, 2) void lf_attn_bwd_kv_kernel(BwdArgs a) {
+  constexpr int CH = D / 8;
+  constexpr int KS = D / 16;
+  constexpr int MB = D / 32;
+  constexpr int RPI = 64 / CH;              // tile rows one wavefront load instruction covers
+  constexpr int LPW = 32 / (RPI * 4);       // load instructions per wavefront, per tensor, per half tile
+  constexpr int T32 = 32 * CH;              // uint4 per half tile (32 rows)
+  static_assert(LPW == 1 || LPW == 2, "a half tile splits over four wavefronts");
+
+  __shared__ uint4 buf[3][2 * T32];         // [half tile mod 3][Q | dO]
+  __shared__ float2 st[3][4][32];           // (lse2, delta) of the 32 streamed rows, one copy per wavefront
+  __shared__ uint4 ph[2][2][2][64];         // P' handoff: [step parity][rh][k-step][lane]
+  __shared__ int2 ent[kPass];
+
+  const int slot = (blockIdx.x & 7) * a.wg_per_xcd + (blockIdx.x >> 3);
+  if (slot >= a.total_wg) return;
+  const int w = a.order[slot];
+  const int h = w / a.owners, r = w % a.owners;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rh = wave & 1, pair = rh;
+  const bool is_ds = wave >= 2;             // role 1: dP', dS', dK
+  const int ln = lane & 31, kg = lane >> 5;
+
+  const int otok0 = (r / a.nb) * a.n + (r % a.nb) * 64;
+  const int o_cnt = min(64, a.n - (r % a.nb) * 64);
+  const int orow = 32 * rh + ln;
+  const bool o_ok = orow < o_cnt;
+  const int32_t* list = a.idx + ((int64_t)h * a.owners + r) * a.list_stride;
+  const int n_ent = a.cnt[(int64_t)h * a.owners + r];
+
+  // owner operand: K rows for role 0 (scores), V rows for role 1 (dP')
+  Frag of[KS];
+  {
+    const uint16_t* op = is_ds ? a.Y + (int64_t)h * a.y_head + (int64_t)(otok0 + orow) * a.y_tok
+                               : a.X + (int64_t)h * a.x_head + (int64_t)(otok0 + orow) * a.x_tok;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      of[s].u = o_ok ? *reinterpret_cast<const uint4*>(op + s * 16 + kg * 8) : make_uint4(0, 0, 0, 0);
+  }
+
+  const char* A1h = reinterpret_cast<const char*>(a.A1 + (int64_t)h * a.a1_head);
+  const char* A2h = reinterpret_cast<const char*>(a.A2 + (int64_t)h * a.a2_head);
+  const char* STh = reinterpret_cast<const char*>(a.stats + (int64_t)h * a.q_len);
+  const uint32_t a1_row_bytes = (uint32_t)(a.a1_tok * 2), a2_row_bytes = (uint32_t)(a.a2_tok * 2);
+
+  // tile loads: wavefront `wave` fills rows [8 wave, +8) of a half tile with LPW instructions
+  const int ld_r = lane / CH, ld_p = lane % CH;
+  uint32_t off1[LPW], off2[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int row = RPI * (LPW * wave + i) + ld_r;
+    off1[i] = (uint32_t)row * a1_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
+    off2[i] = (uint32_t)row * a2_row_bytes + (uint32_t)swz<CH>(row, ld_p) * 16u - 1024u * i;
+  }
+  const uint32_t st_off = (uint32_t)lane * 4u;
+  auto rsrc = [](const char* base, uint32_t row_bytes, int first, int count) {
+    int32x4 rs;
+    const uint64_t b = (uint64_t)base + (uint64_t)(uint32_t)first * row_bytes;
+    rs[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    rs[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
+    rs[2] = __builtin_amdgcn_readfirstlane((int)((uint32_t)count * row_bytes));
+    rs[3] = 0x00020000;
+    return rs;
+  };
+  auto fetch = [&](int32x4 rs, uint4* dst, const uint32_t (&off)[LPW]) __attribute__((always_inline)) {
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)LDS_PTR(void, dst + RPI * LPW * wave * CH));
+    if constexpr (LPW == 2)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds"
+                   :: "s"(lds0), "v"(off[0]), "v"(off[1]), "s"(rs) : "memory", "m0");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                   "buffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(lds0), "v"(off[0]), "s"(rs) : "memory", "m0");
+  };
+  // half tile t of the pass: list entry t/2, rows [32 (t&1), +32) of its block
+  auto half = [&](int t) {
+    const int2 e = ent[t >> 1];
+    const int2 u = make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+    return (t & 1) ? make_int2(u.x + 32, max(u.y - 32, 0)) : make_int2(u.x, min(u.y, 32));
+  };
+  // half tile t -> stage t mod 3: the Q and dO rows and the (lse2, delta) pairs (every wavefront its own copy)
+  auto request = [&](int t, int stage) __attribute__((always_inline)) {
+    const int2 e = half(t);
+    fetch(rsrc(A1h, a1_row_bytes, e.x, e.y), buf[stage], off1);
+    fetch(rsrc(A2h, a2_row_bytes, e.x, e.y), buf[stage] + T32, off2);
+    const int32x4 rs = rsrc(STh, 8u, e.x, e.y);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(void, st[stage][wave]));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                 "buffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(lds0), "v"(st_off), "s"(rs) : "memory", "m0");
+  };
+
+  int raddr[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) raddr[s] = ln * CH + swz<CH>(ln, 2 * s + kg);
+  int tbase[MB];
+  {
+    const int i16 = lane & 15;
+    const int tr_row = 4 * kg + (i16 >> 2);
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int col = 32 * mb + tr_col;
+      tbase[mb] = (tr_row * CH + swz<CH>(tr_row, col >> 3)) * 8 + (col & 7);
+    }
+  }
+  auto tfrag = [&](const uint4* tile, int u, int mb) __attribute__((always_inline)) {
+    const uint16_t* p16 = reinterpret_cast<const uint16_t*>(tile);
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p16 + tbase[mb] + (16 * u) * CH * 8));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        LDS_PTR(bf16x4, p16 + (tbase[mb] ^ kTrHiFlip<CH>) + (16 * u + 8) * CH * 8));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+
+  f32x16 acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mb][i] = 0.0f;
+  f32x16 zero16;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
+
+  // the score-like product of this wavefront's role: rows of `tile` times the owner operand
+  auto product = [&](const uint4* tile) __attribute__((always_inline)) {
+    constexpr int HB = KS / 2;
+    Frag f[HB];
+    f32x16 c = zero16;
+#pragma unroll
+    for (int s = 0; s < HB; ++s) f[s].u = tile[raddr[s]];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < HB; ++s) {
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[s].v, of[s].v, c, 0, 0, 0);
+      f[s].u = tile[raddr[HB + s]];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int s = 0; s < HB; ++s) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[s].v, of[HB + s].v, c, 0, 0, 0);
+    return c;
+  };
+  // acc += tile^T (transposing reads) times b[0], b[1]
+  auto accumulate = [&](const uint4* tile, const bf16x8 (&b)[2]) __attribute__((always_inline)) {
+    bf16x8 tf[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) tf[mb] = tfrag(tile, 0, mb);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], b[0], acc[mb], 0, 0, 0);
+      tf[mb] = tfrag(tile, 1, mb);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+      acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[mb], b[1], acc[mb], 0, 0, 0);
+  };
+  // accumulator i of a score tile is streamed row 8 (i/4) + 4 kg + i%4; the (lse2, delta)
+  // pairs of rows 8 g + 4 kg .. + 3 are two 16-byte reads
+  auto stats4 = [&](const float2* strow, int g, float (&lse)[4], float (&dl)[4]) __attribute__((always_inline)) {
+    const float4 sa = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg);
+    const float4 sb = *reinterpret_cast<const float4*>(strow + 8 * g + 4 * kg + 2);
+    lse[0] = sa.x; lse[1] = sa.z; lse[2] = sb.x; lse[3] = sb.z;
+    dl[0] = sa.y; dl[1] = sa.w; dl[2] = sb.y; dl[3] = sb.w;
+  };
+
+  for (int l0 = 0; l0 < n_ent; l0 += kPass) {
+    const int n_local = min(n_ent - l0, kPass);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    for (int i = tid; i < n_local; i += kKvThreads) {
+      const int cidx = list[l0 + i];
+      const bool ok = (unsigned)cidx < (unsigned)a.streams;
+      const int tau = ok ? cidx / a.nb : 0, j = ok ? cidx % a.nb : 0;
+      ent[i] = make_int2(tau * a.n + j * 64, ok ? min(64, a.n - j * 64) : 0);
+    }
+    __syncthreads();
+
+    // Step t: half tile t is in stage t mod 3 (requested a step ago), half tile t-1 still in its
+    // stage.  Role 0 works on t; role 1 forms dP' of t and finishes t-1 with the P' its partner
+    // left during step t-1.  The first step has nothing to finish and the last one only finishes,
+    // so they are peeled off and the loop body has no condition but the role.
+    const int steps = 2 * n_local;
+    f32x16 dp_prev = zero16;
+    int cur = 0, nxt = 1, prv = 2;
+    auto rotate = [&]() { const int was = prv; prv = cur; cur = nxt; nxt = was; };
+    // role 0 on half tile t (stage cur): S', P' (handed over), dV^T += dO^T P'
+    auto p_step = [&](int t) __attribute__((always_inline)) {
+      const int cnt = half(t).y;
+      const f32x16 sacc = product(buf[cur]);
+      bf16x8 pf[2];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float lse[4], dl[4];
+        stats4(st[cur][wave], g, lse, dl);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * g + e, row = 8 * g + 4 * kg + e;
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse[e]));
+          if (row >= cnt) p = 0.0f;
+          pf[i >> 3][i & 7] = (__bf16)p;
+        }
+      }
+      ph[t & 1][pair][0][lane] = __builtin_bit_cast(uint4, pf[0]);
+      ph[t & 1][pair][1][lane] = __builtin_bit_cast(uint4, pf[1]);
+      accumulate(buf[cur] + T32, pf);
+    };
+    // role 1 finishing half tile t (stage prv): dS' = P' (dP' - delta), dK^T += Q^T dS'
+    auto ds_finish = [&](int t) __attribute__((always_inline)) {
+      bf16x8 pf[2], dsf[2];
+      pf[0] = __builtin_bit_cast(bf16x8, ph[t & 1][pair][0][lane]);
+      pf[1] = __builtin_bit_cast(bf16x8, ph[t & 1][pair][1][lane]);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float lse[4], dl[4];
+        stats4(st[prv][wave], g, lse, dl);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * g + e;
+          dsf[i >> 3][i & 7] = (__bf16)((float)pf[i >> 3][i & 7] * (dp_prev[i] - dl[e]));
+        }
+      }
+      accumulate(buf[prv], dsf);
+    };
+    request(0, 0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    lds_barrier();
+    request(1, nxt);                       // steps >= 2: a list entry is two half tiles
+    if (!is_ds) p_step(0); else dp_prev = product(buf[cur] + T32);
+    rotate();
+    for (int t = 1; t < steps; ++t) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      lds_barrier();
+      if (t + 1 < steps) request(t + 1, nxt);
+      if (!is_ds) {
+        p_step(t);
+      } else {
+        const f32x16 dp_cur = product(buf[cur] + T32);   // dP' of half tile t
+        ds_finish(t - 1);
+        dp_prev = dp_cur;
+      }
+      rotate();
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    lds_barrier();
+    if (is_ds) ds_finish(steps - 1);
+  }
+
+  // accumulator i of acc[mb] is channel 32 mb + 8 (i/4) + 4 kg + i%4 of the owner row
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  if (o_ok) {
+    uint16_t* op = is_ds ? a.out1 + (int64_t)h * a.o1_head + (int64_t)(otok0 + orow) * a.o1_tok
+                         : a.out2 + (int64_t)h * a.o2_head + (int64_t)(otok0 + orow) * a.o2_tok;
+    const float factor = is_ds ? a.scale : 1.0f;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -508,10 +749,10 @@ int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* 
   a.total_wg = dm->H * dm->n_q;
   a.wg_per_xcd = (a.total_wg + 7) / 8;
   hipError_t rc = dm->d == 128
-      ? lf_launch(lf_attn_bwd_kernel<128, 0>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
-      : lf_launch(lf_attn_bwd_kernel<64, 0>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
+      ? lf_launch(lf_attn_bwd_q_kernel<128>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a)
+      : lf_launch(lf_attn_bwd_q_kernel<64>, dim3((unsigned)(a.wg_per_xcd * 8)), dim3(kThreads), 0, st, a);
   if (rc != hipSuccess) return LF_ERR_HIP;
-  // dK, then dV
+  // dK and dV
   a.X = (const uint16_t*)K;   a.x_tok = s->k_stride_tok;  a.x_head = s->k_stride_head;
   a.Y = (const uint16_t*)V;   a.y_tok = s->v_stride_tok;  a.y_head = s->v_stride_head;
   a.A1 = (const uint16_t*)Q;  a.a1_tok = s->q_stride_tok; a.a1_head = s->q_stride_head;
@@ -527,10 +768,7 @@ int lf_launch_attn_bwd(const void* Q, const void* K, const void* V, const void* 
     return LF_ERR_HIP;
   a.order = order;
   const dim3 grid2((unsigned)(a.wg_per_xcd * 8));
-  rc = dm->d == 128 ? lf_launch(lf_attn_bwd_kernel<128, 1>, grid2, dim3(kThreads), 0, st, a)
-                    : lf_launch(lf_attn_bwd_kernel<64, 1>, grid2, dim3(kThreads), 0, st, a);
-  if (rc != hipSuccess) return LF_ERR_HIP;
-  rc = dm->d == 128 ? lf_launch(lf_attn_bwd_kernel<128, 2>, grid2, dim3(kThreads), 0, st, a)
-                    : lf_launch(lf_attn_bwd_kernel<64, 2>, grid2, dim3(kThreads), 0, st, a);
+  rc = dm->d == 128 ? lf_launch(lf_attn_bwd_kv_kernel<128>, grid2, dim3(kKvThreads), 0, st, a)
+                    : lf_launch(lf_attn_bwd_kv_kernel<64>, grid2, dim3(kKvThreads), 0, st, a);
   return rc == hipSuccess ? LF_OK : LF_ERR_HIP;
 }
