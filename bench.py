@@ -163,6 +163,18 @@ def measured_peaks(torch, select_bytes: int):
     for name, rnd in (("mfma_bf16_loop_constant_operands_tflops", 0), ("mfma_bf16_loop_random_operands_tflops", 1)):
         t = timed(lambda: lib.lfb_mfma_loop(4000, rnd, sink.data_ptr(), C.byref(flop), st), 5)
         out[name] = flop.value / t / 1e12
+    # the attention step's instruction mix without memory: matrix instructions alone, the vector
+    # work of the softmax alone, both in every wavefront (microseconds per launch of 2000 steps)
+    lib.lfb_issue_mix.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    for wps in (2, 4):   # wavefronts per SIMD
+        mix = {}
+        for name, what in (("mfma_only_us", 1), ("softmax_valu_only_us", 2), ("both_us", 3)):
+            mix[name] = timed(lambda: lib.lfb_issue_mix(what, 2000, wps, sink.data_ptr(), st), 5) * 1e6
+        mix["overlap"] = (mix["mfma_only_us"] + mix["softmax_valu_only_us"] - mix["both_us"]) / \
+            min(mix["mfma_only_us"], mix["softmax_valu_only_us"])
+        # 16 matrix instructions of 2*32*32*16 FLOP per wavefront and step
+        mix["both_tflops"] = 256 * 4 * wps * 2000 * 16 * 2.0 * 32 * 32 * 16 / (mix["both_us"] * 1e-6) / 1e12
+        out[f"issue_mix_16_mfma_plus_softmax_step_{wps}_waves_per_simd"] = mix
     return out
 
 
