@@ -208,7 +208,43 @@ def test_full_size_last_chunk_one_head_against_oracle(gpu):
     lists = idx.cpu().numpy()
     print(f"full size: H={w.heads} n={w.frame_len} F={w.frames} list_len={lists.shape[-1]}", flush=True)
     (dQ, dK, dV), _ = _run(torch, lf, w, x, lists)
+    # every head: what holds at any size.  The rows of P sum to one, so the token sums of dV
+    # equal those of dO; the rows of dS sum to zero (delta is the P-weighted mean of dP), so the
+    # token sums of dK vanish.  Sums of 32 760 bfloat16-rounded terms: absolute slack below.
+    dOf = _f32(x["dO"]).astype(np.float64)
+    dv_err = np.abs(dV.sum(axis=1) - dOf.sum(axis=1)).max()
+    dk_err = np.abs(dK.sum(axis=1)).max()
+    print(f" all heads: |sum dV - sum dO| {dv_err:.3f}, |sum dK| {dk_err:.3f}", flush=True)
+    assert dv_err <= 0.5 and dk_err <= 0.5
     for h in (0, 7):
+        sl = slice(h, h + 1)
+        rQ, rK, rV = O.sparse_attention_backward(_f32(x["Q"][sl]), _f32(x["K"][sl]), _f32(x["V"][sl]),
+                                                 _f32(x["dO"][sl]), lists[sl], w.frame_len, w.block)
+        print(f" head {h}", flush=True)
+        _close("dQ", dQ[sl], rQ)
+        _close("dK", dK[sl], rK)
+        _close("dV", dV[sl], rV)
+
+
+def test_rollout_call_40_heads(gpu):
+    """One call of the 40-head rollout (chunk 4, the shape of the model's full attention layer):
+    the token-sum properties on every head, the oracle on the first and the last head."""
+    torch, lf = gpu
+    w = synth.cfg_rollout(4, 1)
+    x = synth.make_inputs(w)
+    x["dO"] = synth.make_upstream_grad(w)
+    Q, K = _dev(torch, x["Q"]), _dev(torch, x["K"])
+    b = lf.lf_chunk_budget(w.chunk_idx, w.schedule)
+    lists = lf.lf_select_mask(Q, K, w.frame_len, w.block, b).cpu().numpy()
+    del Q, K
+    print(f"rollout call: H={w.heads} n={w.frame_len} F={w.frames} list_len={lists.shape[-1]}", flush=True)
+    (dQ, dK, dV), _ = _run(torch, lf, w, x, lists)
+    dOf = _f32(x["dO"]).astype(np.float64)
+    dv_err = np.abs(dV.sum(axis=1) - dOf.sum(axis=1)).max()
+    dk_err = np.abs(dK.sum(axis=1)).max()
+    print(f" all heads: |sum dV - sum dO| {dv_err:.3f}, |sum dK| {dk_err:.3f}", flush=True)
+    assert dv_err <= 0.5 and dk_err <= 0.5
+    for h in (0, w.heads - 1):
         sl = slice(h, h + 1)
         rQ, rK, rV = O.sparse_attention_backward(_f32(x["Q"][sl]), _f32(x["K"][sl]), _f32(x["V"][sl]),
                                                  _f32(x["dO"][sl]), lists[sl], w.frame_len, w.block)
