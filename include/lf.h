@@ -255,9 +255,11 @@ int lf_sparse_attn_split(const void* Q, const void* Kcache, const void* Vcache,
  *                  call wrote it.
  *   lse2           device, float32 [H][q_len], as the forward call wrote it.
  *   indices        device, int32 [H][n_q][list_len], the forward call's lists.  Every list must
- *                  be ascending without duplicates among its valid ids (what lf_select_mask
- *                  writes); this is not checked, and other lists give wrong dK and dV.  Ids
- *                  outside [0, n_k) are skipped.
+ *                  be strictly ascending as a whole, compared as signed integers (what
+ *                  lf_select_mask writes; ids outside [0, n_k) are skipped, so negative ones may
+ *                  only lead and ids >= n_k only trail).  This is not checked: the key-major
+ *                  launch finds the query blocks that keep a KV block by bisection, and lists
+ *                  in another order or with repeated ids give wrong dK and dV.
  *   dQ             device, bfloat16, written, with the q_ strides.
  *   dK, dV         device, bfloat16, written for every KV token (zeros where no list keeps the
  *                  token's block), with the k_ and v_ strides.
