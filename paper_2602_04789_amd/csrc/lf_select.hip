@@ -155,26 +155,49 @@ inline size_t select_lds_bytes(const SelectArgs& a, int e) {
   return b;
 }
 
-// <q_tilde, row> over the head dimension in ascending order, binary64 accumulate (the product
+// <q_tilde, row c> over the head dimension in ascending order, binary64 accumulate (the product
 // of two float32 is exact in binary64, so only the order matters), rounded to float32 once.
-// `row` points at channel quad 0 of the row in a quad-major matrix with `rows` rows.
+// `base` points at row 0, channel quad 0 of a quad-major matrix with `rows` rows and is the
+// same for the whole workgroup, so the quad's address is a scalar base plus the lane's 16 c.
+// Sixteen of the row's channel quads are in flight at any time: four groups of four, each
+// group requested again as soon as it has been used, so that the load latency is paid once.
 template <int D>
 __device__ __forceinline__ float dot_quad_major(const double* __restrict__ qd,
-                                                const float4* __restrict__ row, int rows) {
+                                                const float4* __restrict__ base, uint32_t c, int rows) {
+  constexpr int G = 4, NG = D / 4 / G;
+  static_assert(NG >= 4, "the ring holds four groups");
+  float4 v[4][G];
   double acc = 0.0;
-#pragma unroll 1
-  for (int q0 = 0; q0 < D / 4; q0 += 16) {
-    float4 v[16];
+  // q_tilde is read through an offset the compiler cannot see through (always 0): called from
+  // a loop, its 2 d registers' worth of reads would otherwise be hoisted out of the loop
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  const double* __restrict__ q = qd + z;
+  auto fetch = [&](float4 (&x)[G], int g, uint32_t cc) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = row[(int64_t)(q0 + u) * rows];
+    for (int u = 0; u < G; ++u) x[u] = (base + (int64_t)(g * G + u) * rows)[cc];
+  };
+  auto use = [&](const float4 (&x)[G], int g) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int t = 4 * (q0 + u);
-      acc += qd[t + 0] * (double)v[u].x;
-      acc += qd[t + 1] * (double)v[u].y;
-      acc += qd[t + 2] * (double)v[u].z;
-      acc += qd[t + 3] * (double)v[u].w;
+    for (int u = 0; u < G; ++u) {
+      const int t = 4 * (g * G + u);
+      acc += q[t + 0] * (double)x[u].x;
+      acc += q[t + 1] * (double)x[u].y;
+      acc += q[t + 2] * (double)x[u].z;
+      acc += q[t + 3] * (double)x[u].w;
     }
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fetch(v[i], i, c);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    use(v[g & 3], g);
+    // An empty statement that takes the sum so far and hands back the row index: the sum cannot
+    // sink below it and the next request cannot rise above it, which keeps the ring as written
+    // (left to itself the compiler gathers all loads first and spills).
+    uint32_t cc = c;
+    asm volatile("" : "+v"(acc), "+v"(cc));
+    if (g + 4 < NG) fetch(v[g & 3], g + 4, cc);
   }
   return (float)acc;
 }
@@ -251,12 +274,11 @@ __device__ __forceinline__ void bitonic_sort(float (&s)[E], int (&p)[E], float* 
   }
 }
 
-// 64-bit key whose unsigned order is the ranks_before order: larger score first (float32
-// bits made monotonic; -0.0 folded onto +0.0 so the two tie), then lower position.
-__device__ __forceinline__ unsigned long long rank_key(float score, int pos) {
-  uint32_t u = __float_as_uint(score + 0.0f);
-  u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
-  return ((unsigned long long)u << 32) | (uint32_t)(0x7fffffff - pos);
+// 32-bit key whose unsigned order is the score order: float32 bits made monotonic, -0.0
+// folded onto +0.0 so that the two tie (ties go to the lower position, see ranks_before).
+__device__ __forceinline__ uint32_t rank_key32(float score) {
+  const uint32_t u = __float_as_uint(score + 0.0f);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
 template <int D, int E>
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   const bool retrieve = a.k_frames < a.m;
   if (retrieve) {
     const float4* khh = reinterpret_cast<const float4*>(a.kh + (int64_t)h * a.kh_rows * D) + a.kh_row0;
-    for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh + c, a.kh_rows);
+    for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh, (uint32_t)c, a.kh_rows);
   }
   __syncthreads();
 
@@ -316,7 +338,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
       p[e] = 0x7fffffff;
       if (i < a.n_cand) {
         const int c = flist[i / a.nb] * a.nb + i % a.nb;
-        s[e] = dot_quad_major<D>(qd, kth + c, a.kt_rows);
+        s[e] = dot_quad_major<D>(qd, kth, (uint32_t)c, a.kt_rows);
         p[e] = i;
         sel[i] = 0;
       }
@@ -327,18 +349,42 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   // candidate per thread the rank is counted directly (how many keys are larger, keys read
   // as LDS broadcasts); larger candidate sets are sorted, after which index = rank.
   if (a.k_blocks < a.n_cand && E == 1) {
-    unsigned long long* keys = reinterpret_cast<unsigned long long*>(xs);   // [256], 8-byte aligned
-    const unsigned long long mine = rank_key(s[0], p[0]);
-    keys[tid] = mine;
+    // 32-bit keys in position order.  A candidate's rank = earlier positions with a key >= its
+    // own + later positions with a key > its own; for a wavefront the positions before its
+    // first lane are all earlier and those after its last lane all later, so only the 64
+    // positions of its own lanes need the position compared.  Pads hold 0, which no key is below.
+    uint32_t* keys = reinterpret_cast<uint32_t*>(xs);   // [256], 16-byte aligned
+    const uint32_t mine = rank_key32(s[0]);
+    keys[tid] = tid < a.n_cand ? mine : 0u;
     __syncthreads();
-    int rank = 0;
-    const int n2 = (a.n_cand + 1) & ~1;   // keys[n_cand] is a pad (smallest key) when n_cand is odd
-    for (int j = 0; j < n2; j += 2) {
-      const ulonglong2 kk = *reinterpret_cast<const ulonglong2*>(keys + j);
-      rank += kk.x > mine ? 1 : 0;
-      rank += kk.y > mine ? 1 : 0;
+    const int w0 = __builtin_amdgcn_readfirstlane(tid & ~63);
+    if (w0 < a.n_cand) {
+      // four counters, so that a compare and the add that takes its carry need not be neighbours
+      int r0 = 0, r1 = 0, r2 = 0, r3 = 0;
+#pragma unroll 4
+      for (int j = 0; j < w0; j += 4) {
+        const uint4 kk = *reinterpret_cast<const uint4*>(keys + j);
+        r0 += kk.x >= mine ? 1 : 0; r1 += kk.y >= mine ? 1 : 0;
+        r2 += kk.z >= mine ? 1 : 0; r3 += kk.w >= mine ? 1 : 0;
+      }
+      const int lane = tid & 63;
+#pragma unroll 4
+      for (int j = 0; j < 64; j += 4) {
+        const uint4 kk = *reinterpret_cast<const uint4*>(keys + w0 + j);
+        r0 += (kk.x > mine || (kk.x == mine && j + 0 < lane)) ? 1 : 0;
+        r1 += (kk.y > mine || (kk.y == mine && j + 1 < lane)) ? 1 : 0;
+        r2 += (kk.z > mine || (kk.z == mine && j + 2 < lane)) ? 1 : 0;
+        r3 += (kk.w > mine || (kk.w == mine && j + 3 < lane)) ? 1 : 0;
+      }
+#pragma unroll 4
+      for (int j = w0 + 64; j < a.n_cand; j += 4) {
+        const uint4 kk = *reinterpret_cast<const uint4*>(keys + j);
+        r0 += kk.x > mine ? 1 : 0; r1 += kk.y > mine ? 1 : 0;
+        r2 += kk.z > mine ? 1 : 0; r3 += kk.w > mine ? 1 : 0;
+      }
+      const int rank = (r0 + r1) + (r2 + r3);
+      if (tid < a.n_cand && rank < a.k_blocks) sel[tid] = 1;
     }
-    if (tid < a.n_cand && rank < a.k_blocks) sel[tid] = 1;
   } else if (a.k_blocks < a.n_cand) {
     bitonic_sort<E>(s, p, xs, xp);
     __syncthreads();
