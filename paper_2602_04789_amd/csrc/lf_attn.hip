@@ -6,8 +6,8 @@
 // wavefronts, and there is no merge at the end.  A workgroup holds two such query blocks and two
 // workgroups share a compute unit, so every SIMD holds two wavefronts, free to be in different
 // parts of their step (the matrix core of one beside the vector ALU of the other).  Each listed
-// KV block is taken as two half
-// tiles of 32 KV rows: the 32 x d K and V half tiles are brought into a double-buffered LDS
+// KV block is taken as half tiles of 32 KV rows (two, or one when the block has at most 32
+// tokens): the 32 x d K and V half tiles are brought into a double-buffered LDS
 // stage by asynchronous global->LDS loads, a wavefront's share of a half tile in one group
 // (V of the next step right after the barrier, K of the step after that after the first
 // half of the score product).
@@ -127,7 +127,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
 
   __shared__ uint4 buf0_all[QPW][2 * TILE];          // K | V of even tiles
   __shared__ uint4 buf1_all[QPW][2 * TILE];          // K | V of odd tiles
-  __shared__ int2 ent_all[QPW][DENSE ? 1 : kMaxEnt / 2];   // (first token, token count) per list entry of a pass
+  __shared__ int2 ent_all[QPW][DENSE ? 1 : kMaxEnt];   // (first token, token count <= 32) per half tile of a pass
+  __shared__ int nh_all[QPW][WPQ];                      // half tiles the wavefronts decoded in a pass
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
   // (head, query block) pairs so that neighbours sharing KV blocks share an L2.
@@ -144,6 +145,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   uint4* const buf0 = buf0_all[qb];
   uint4* const buf1 = buf1_all[qb];
   int2* const ent = ent_all[qb];
+  int* const nh_mine = nh_all[qb];
 
   const int tid = threadIdx.x % kThreads, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront inside its query block, in a scalar register
@@ -159,15 +161,18 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   // The list entries of the first pass are requested first, so that they travel together with
   // the Q fragments instead of after them.
   const int32_t* list = DENSE ? nullptr : a.idx + ((int64_t)h * a.n_q + r) * a.list_stride;
-  constexpr int EPT = DENSE ? 1 : kMaxEnt / 2 / kThreads;   // list entries per thread and pass (two half tiles each)
+  constexpr int EPT = DENSE ? 1 : kMaxEnt / 2 / kThreads;   // list entries per thread and pass (up to two half tiles each)
   int pre[EPT];
   if constexpr (!DENSE) {
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-      const int i = tid + j * kThreads;
+      const int i = EPT * tid + j;
       pre[j] = i < a.list_len ? list[i] : -1;
     }
   }
+  // A wavefront whose 32 query rows all lie past the end of a short query block loads its share
+  // of the tiles and keeps the barriers, but computes nothing.
+  const bool active = DENSE || 32 * rh < q_cnt;
 
   // Q^T fragments (B operand): lane (column q = ln, k-group kg) holds 8 consecutive channels.
   Frag qf[KS];
@@ -201,14 +206,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
     koff[i] = (uint32_t)row * (uint32_t)k_row_bytes + (uint32_t)k_swz<CH>(row, ld_p) * 16u - 1024u * i;
     voff[i] = (uint32_t)row * (uint32_t)v_row_bytes + (uint32_t)v_swz<CH>(row, ld_p) * 16u - 1024u * i;
   }
-  // (first token, token count) of list entry t, wavefront-uniform.
-  auto entry = [&](int i) -> int2 {
-    const int2 e = ent[i & (kMaxEnt / 2 - 1)];
-    return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+  // (first token, token count) of half tile i of the pass, wavefront-uniform; past the pass's
+  // last half tile an empty one (count 0: its loads touch no memory and its scores are masked).
+  int nh_q = 0;   // half tiles of this query block in the current pass
+  auto hent_finish = [&](int2 e, int i) -> int2 {
+    const bool in = i < nh_q;
+    return make_int2(__builtin_amdgcn_readfirstlane(in ? e.x : 0), __builtin_amdgcn_readfirstlane(in ? e.y : 0));
   };
-  // the two half tiles of a list entry: 32 rows each, the second starts 32 tokens further
-  auto lower = [](int2 e) { return make_int2(e.x, min(e.y, 32)); };
-  auto upper = [](int2 e) { return make_int2(e.x + 32, max(e.y - 32, 0)); };
+  auto hent = [&](int i) -> int2 { return hent_finish(ent[i & (kMaxEnt - 1)], i); };
   // The loads are raw buffer loads whose resource is the tile itself: base = the block's
   // first token, num_records = its token count x the row pitch.  Rows past a short block's
   // count are then out of range, which touches no memory and writes zeros, so the loads need
@@ -316,8 +321,12 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
     }
   }
 
-  // Lists are decoded kMaxEnt / 2 entries at a time into LDS: block id -> two half tiles
-  // (first token, count); an id outside [0, n_k) becomes two empty ones (count 0).
+  // Lists are decoded kMaxEnt / 2 entries at a time into LDS: block id -> its half tiles of 32
+  // KV rows (first token, count), one for a block of at most 32 tokens, two otherwise, none
+  // for an id outside [0, n_k); the half tiles of a pass are stored back to back, so a step is
+  // never spent on an empty upper half.  The query blocks of a workgroup share the barriers and
+  // therefore take the same number of steps: the longer one's, rounded up to an even number,
+  // the shorter one ending on empty half tiles.
   // The dense kernel has no list: half tile t is KV tokens [kv0 + 32 t, +32) cut at kv1 (empty
   // beyond it), all in one pass of an even number of steps.
   auto dense_half = [&](int t) {
@@ -328,35 +337,65 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
   const int pass_len = DENSE ? n_entries : kMaxEnt / 2;
   for (int l0 = 0; l0 < n_entries; l0 += pass_len) {
     const int l1 = min(n_entries, l0 + pass_len);
-    const int t0 = 2 * l0, t1 = 2 * l1;   // half-tile steps of this pass
+    int nsteps = 2 * (l1 - l0);   // half-tile steps of this pass
     if constexpr (!DENSE) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-      __syncthreads();
+      int htok[EPT], hcnt[EPT], halves = 0;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        const int i = l0 + tid + e * kThreads;
-        if (i < l1) {
-          const int c = l0 == 0 ? pre[e] : list[i];
-          const bool ok = (unsigned)c < (unsigned)a.n_k;
-          const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
-          const int cnt = ok ? min(64, a.n - j * 64) : 0;
-          ent[i - l0] = make_int2(tau * a.n + j * 64, cnt);
-        }
+        const int i = l0 + EPT * tid + e;
+        const int c = i < l1 ? (l0 == 0 ? pre[e] : list[i]) : -1;
+        const bool ok = (unsigned)c < (unsigned)a.n_k;
+        const int tau = ok ? c / a.nb : 0, j = ok ? c % a.nb : 0;
+        htok[e] = tau * a.n + j * 64;
+        hcnt[e] = ok ? min(64, a.n - j * 64) : 0;
+        halves += hcnt[e] > 32 ? 2 : (hcnt[e] > 0 ? 1 : 0);
+      }
+      // inclusive prefix of `halves` over the wavefront, then over the wavefronts through LDS
+      int incl = halves;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+      }
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __syncthreads();   // the previous pass no longer reads ent / nh_all, its tile loads have landed
+      if (lane == 63) nh_mine[wave] = incl;
+      __syncthreads();
+      int pos = incl - halves;
+      nh_q = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < WPQ; ++w2) {
+        const int n = nh_mine[w2];
+        if (w2 < wave) pos += n;
+        nh_q += n;
+      }
+      nh_q = __builtin_amdgcn_readfirstlane(nh_q);
+      int longest = 0;
+#pragma unroll
+      for (int q2 = 0; q2 < QPW; ++q2) {
+        int n = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < WPQ; ++w2) n += nh_all[q2][w2];
+        longest = max(longest, n);
+      }
+      nsteps = __builtin_amdgcn_readfirstlane((longest + 1) & ~1);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        if (hcnt[e] > 0) ent[pos++] = make_int2(htok[e], min(hcnt[e], 32));
+        if (hcnt[e] > 32) ent[pos++] = make_int2(htok[e] + 32, hcnt[e] - 32);
       }
       __syncthreads();
+      if (nsteps == 0) continue;   // no valid id in this pass, for any query block of the workgroup
     }
     // Software pipeline, one step deep (a step, "tile" below, is one half tile of 32 KV rows):
     // iteration t computes S^T of tile t+1 (matrix core)
     // next to the softmax of tile t (vector ALU), then O^T += V^T P^T of tile t.  In flight
     // while it runs: K of tile t+2 and V of tile t+1.  Buffer t&1 holds K_t and V_t.
-    int2 eb = make_int2(0, 0);   // list entry whose half tiles are requested next
     int2 e0, e1, e2;
     if constexpr (DENSE) {
       e0 = dense_half(0); e1 = dense_half(1); e2 = dense_half(2);
     } else {
-      const int2 eb0 = entry(l0);
-      eb = entry(min(l0 + 1, l1 - 1));
-      e0 = lower(eb0); e1 = upper(eb0); e2 = lower(eb);
+      e0 = hent(0); e1 = hent(1); e2 = hent(2);
     }
     fetch_k(k_rsrc(e0), buf0);
     fetch_v(v_rsrc(e0), buf0);
@@ -380,12 +419,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
     for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
     f32x16 sacc = s_half(buf0, s_half(buf0, zero16, 0), KS / 2);
 
-    // Past the end of the list the pipeline runs on the last entry again: its loads and its
-    // S^T are redundant and unused, which keeps the loop body free of branches.
-    auto tile = [&](int t, uint4* cur, uint4* other, bool second) __attribute__((always_inline)) {
+    // Past the pass's last half tile the pipeline runs on empty ones: their loads touch no memory
+    // and their S^T is unused, which keeps the loop body free of branches.
+    auto tile = [&](int t, uint4* cur, uint4* other) __attribute__((always_inline)) {
       const int cnt = e0.y;
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wavefront's share of K_{t+1}, V_t has landed
       lds_barrier();                             // ... everyone's has; K_t and V_{t-1} are no longer read
+      // half tile t+3 is looked up now and made wavefront-uniform at the end of the step
+      const int2 e_raw = DENSE ? make_int2(0, 0) : ent[(t + 3) & (kMaxEnt - 1)];
       const int32x4 krs = k_rsrc(e2), vrs = v_rsrc(e1);
       fetch_v(vrs, other);
       // accumulator i of a lane: KV row 8 (i/4) + 4 kg + i%4 of the half tile, query column ln
@@ -503,18 +544,31 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void lf_attn_kernel(AttnArgs
       sacc = snext;
       e0 = e1;
       e1 = e2;
-      if constexpr (DENSE) {
-        e2 = dense_half(t + 3);
-      } else if (second) {   // step t + 3 opens the next list entry
-        eb = entry(min((t + 3) >> 1, l1 - 1));
-        e2 = lower(eb);
-      } else {
-        e2 = upper(eb);
-      }
+      if constexpr (DENSE) e2 = dense_half(t + 3);
+      else e2 = hent_finish(e_raw, t + 3);
     };
-    for (int t = t0; t < t1; t += 2) {
-      tile(t, buf0, buf1, false);
-      tile(t + 1, buf1, buf0, true);
+    // The step of a wavefront without query rows: its share of the loads, and the barrier.
+    auto tile_idle = [&](int t, uint4* cur, uint4* other) __attribute__((always_inline)) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      lds_barrier();
+      const int2 e_raw = ent[(t + 3) & (kMaxEnt - 1)];
+      const int32x4 krs = k_rsrc(e2), vrs = v_rsrc(e1);
+      fetch_v(vrs, other);
+      fetch_k(krs, cur);
+      e0 = e1;
+      e1 = e2;
+      e2 = hent_finish(e_raw, t + 3);
+    };
+    if (active) {
+      for (int t = 0; t < nsteps; t += 2) {
+        tile(t, buf0, buf1);
+        tile(t + 1, buf1, buf0);
+      }
+    } else {
+      for (int t = 0; t < nsteps; t += 2) {
+        tile_idle(t, buf0, buf1);
+        tile_idle(t + 1, buf1, buf0);
+      }
     }
   }
 
