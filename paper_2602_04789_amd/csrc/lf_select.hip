@@ -2,7 +2,8 @@
 //
 //   lf_pool_kernel        block mean pooling of Q and K (Eq. 7, blockwise): the one pass
 //                         over the bf16 inputs, HBM-bound.
-//   lf_frame_mean_kernel  frame means of the candidate frames (Eq. 7, framewise).
+//   lf_frame_mean_kernel  frame means of the candidate frames (Eq. 7, framewise); the block
+//                         means of Q ride along in the same launch.
 //   lf_select_kernel      per (head, query block): frame scores (Eq. 8), frame top-k
 //                         (Eq. 9), block scores (Eq. 10), block top-k by a bitonic sort over
 //                         lane shuffles and LDS (Eq. 11), ascending index list (Eq. 12).
@@ -46,14 +47,11 @@ __device__ __forceinline__ int64_t quad_major(int rows, int c, int t) {
 // One workgroup per block of <= 64 tokens.  Thread t owns 8 consecutive channels
 // (one 16-byte load per token) of every (256/CH)-th token.
 template <int D>
-__global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
+__device__ __forceinline__ void pool_block(const PoolArgs& a, int h, int u, double* lds) {
   constexpr int CH = D / 8;          // 16-byte chunks per token row
   constexpr int RG = kThreads / CH;  // token rows in flight per pass
-  __shared__ double red[RG][D];
+  double (*red)[D] = reinterpret_cast<double (*)[D]>(lds);   // [RG][D]
 
-  const int per_head = a.n_q + a.n_kp;
-  const int h = blockIdx.x / per_head;
-  const int u = blockIdx.x % per_head;
   const bool is_q = u < a.n_q;
   const int c = is_q ? u : a.k_block0 + u - a.n_q;
   const int tau = c / a.nb, j = c % a.nb;
@@ -100,37 +98,62 @@ __global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
   }
 }
 
-// k_hat of frames tau0 .. tau0 + count - 1, written to rows out0 .. of the quad-major matrix
-// kh (kh_rows rows per head): binary64 sum of the frame's nb block means in ascending block
-// order, / nb, rounded to float32.  One thread per channel quad.
-__global__ void lf_frame_mean_kernel(const float* __restrict__ kt, float* __restrict__ kh,
-                                     int d, int nb, int kt_rows, int kh_rows, int tau0, int out0,
-                                     int count) {
-  const int h = blockIdx.x / count, a = blockIdx.x % count;
-  const int tau = tau0 + a;
-  for (int q = threadIdx.x; q < d / 4; q += blockDim.x) {
-    const float4* src = reinterpret_cast<const float4*>(kt + (int64_t)h * kt_rows * d) +
-                        ((int64_t)q * kt_rows + (int64_t)tau * nb);
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int j = 0;
-    for (; j + 8 <= nb; j += 8) {
-      float4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = src[j + u];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        s0 += (double)v[u].x; s1 += (double)v[u].y; s2 += (double)v[u].z; s3 += (double)v[u].w;
-      }
-    }
-    for (; j < nb; ++j) {
-      const float4 v = src[j];
-      s0 += (double)v.x; s1 += (double)v.y; s2 += (double)v.z; s3 += (double)v.w;
-    }
-    float4 o;
-    o.x = (float)(s0 / (double)nb); o.y = (float)(s1 / (double)nb);
-    o.z = (float)(s2 / (double)nb); o.w = (float)(s3 / (double)nb);
-    reinterpret_cast<float4*>(kh + (int64_t)h * kh_rows * d)[(int64_t)q * kh_rows + out0 + a] = o;
+// Bytes of LDS pool_block<D> needs: 16 KB for either head dimension.
+template <int D> constexpr int pool_lds_doubles() { return (kThreads / (D / 8)) * D; }
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void lf_pool_kernel(PoolArgs a) {
+  __shared__ double red[pool_lds_doubles<D>()];
+  const int per_head = a.n_q + a.n_kp;
+  pool_block<D>(a, blockIdx.x / per_head, blockIdx.x % per_head, red);
+}
+
+// k_hat of frames tau0 .. tau0 + count - 1 of every head, written to rows out0 .. of the
+// quad-major matrix kh (kh_rows rows per head): binary64 sum of the frame's nb block means in
+// ascending block order, / nb, rounded to float32.  One workgroup per (head, frame), one thread
+// per channel quad.  The workgroups after the first H * count pool query blocks instead (the
+// block means of Q are not needed before the selection kernel, so they travel with this small
+// launch rather than lengthen the pass over K): workgroup H * count + i is unit i of `qp`.
+struct FrameMeanArgs {
+  const float* kt;
+  float* kh;
+  int nb, kt_rows, kh_rows, tau0, out0, count, H;
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void lf_frame_mean_kernel(FrameMeanArgs f, PoolArgs qp) {
+  __shared__ double red[pool_lds_doubles<D>()];
+  const int n_fm = f.H * f.count;
+  if ((int)blockIdx.x >= n_fm) {
+    const int u = blockIdx.x - n_fm, per_head = qp.n_q + qp.n_kp;
+    pool_block<D>(qp, u / per_head, u % per_head, red);
+    return;
   }
+  const int h = blockIdx.x / f.count, a = blockIdx.x % f.count;
+  const int tau = f.tau0 + a;
+  const int q = threadIdx.x;
+  if (q >= D / 4) return;
+  const float4* src = reinterpret_cast<const float4*>(f.kt + (int64_t)h * f.kt_rows * D) +
+                      ((int64_t)q * f.kt_rows + (int64_t)tau * f.nb);
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  int j = 0;
+  for (; j + 8 <= f.nb; j += 8) {
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[j + u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      s0 += (double)v[u].x; s1 += (double)v[u].y; s2 += (double)v[u].z; s3 += (double)v[u].w;
+    }
+  }
+  for (; j < f.nb; ++j) {
+    const float4 v = src[j];
+    s0 += (double)v.x; s1 += (double)v.y; s2 += (double)v.z; s3 += (double)v.w;
+  }
+  float4 o;
+  o.x = (float)(s0 / (double)f.nb); o.y = (float)(s1 / (double)f.nb);
+  o.z = (float)(s2 / (double)f.nb); o.w = (float)(s3 / (double)f.nb);
+  reinterpret_cast<float4*>(f.kh + (int64_t)h * f.kh_rows * D)[(int64_t)q * f.kh_rows + f.out0 + a] = o;
 }
 
 struct SelectArgs {
@@ -407,10 +430,10 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
 
 }  // namespace
 
-// Pools query blocks (when Q is given) and the KV blocks of frames [frame0, frame1) into qt / the
-// quad-major matrix kt with kt_rows rows per head.
-static hipError_t launch_pool(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
-                        float* kt, int kt_rows, int frame0, int frame1, hipStream_t st) {
+// Arguments for pooling the query blocks (when Q is given) and the KV blocks of frames
+// [frame0, frame1) into qt / the quad-major matrix kt with kt_rows rows per head.
+static PoolArgs pool_args(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
+                          float* kt, int kt_rows, int frame0, int frame1) {
   PoolArgs pa;
   pa.Q = (const uint16_t*)Q;
   pa.K = (const uint16_t*)K;
@@ -426,10 +449,36 @@ static hipError_t launch_pool(const void* Q, const void* K, const lf_shape* s, c
   pa.k_block0 = frame0 * dm->nb;
   pa.n_kp = (frame1 - frame0) * dm->nb;
   pa.kt_rows = kt_rows;
+  return pa;
+}
+
+static hipError_t launch_pool(const void* Q, const void* K, const lf_shape* s, const lf_dims* dm, float* qt,
+                        float* kt, int kt_rows, int frame0, int frame1, hipStream_t st) {
+  const PoolArgs pa = pool_args(Q, K, s, dm, qt, kt, kt_rows, frame0, frame1);
   const unsigned pool_grid = (unsigned)(dm->H * (pa.n_q + pa.n_kp));
   if (pool_grid == 0) return hipSuccess;
   return dm->d == 128 ? lf_launch(lf_pool_kernel<128>, dim3(pool_grid), dim3(kThreads), 0, st, pa)
                       : lf_launch(lf_pool_kernel<64>, dim3(pool_grid), dim3(kThreads), 0, st, pa);
+}
+
+// Frame means of frames [tau0, tau0 + count) of every head, to rows out0 .. of kh; after them,
+// in the same launch, the units of `qp` are pooled (qp.n_q = qp.n_kp = 0: none).
+static hipError_t launch_frame_means(const lf_dims* dm, const float* kt, float* kh, int kt_rows, int kh_rows,
+                                     int tau0, int out0, int count, const PoolArgs& qp, hipStream_t st) {
+  FrameMeanArgs f;
+  f.kt = kt;
+  f.kh = kh;
+  f.nb = dm->nb;
+  f.kt_rows = kt_rows;
+  f.kh_rows = kh_rows;
+  f.tau0 = tau0;
+  f.out0 = out0;
+  f.count = count;
+  f.H = dm->H;
+  const unsigned grid = (unsigned)(dm->H * count + dm->H * (qp.n_q + qp.n_kp));
+  if (grid == 0) return hipSuccess;
+  return dm->d == 128 ? lf_launch(lf_frame_mean_kernel<128>, dim3(grid), dim3(kThreads), 0, st, f, qp)
+                      : lf_launch(lf_frame_mean_kernel<64>, dim3(grid), dim3(kThreads), 0, st, f, qp);
 }
 
 static hipError_t launch_select(const lf_budget* b, const lf_dims* dm, const float* qt, const float* kt,
@@ -485,11 +534,13 @@ int lf_launch_select(const void* Q, const void* K, const lf_shape* s, const lf_b
   float* qt = (float*)(ws + dm->off_qt);
   float* kt = (float*)(ws + dm->off_kt);
   float* kh = (float*)(ws + dm->off_kh);
-  if (launch_pool(Q, K, s, dm, qt, kt, dm->n_k, 0, dm->F, st) != hipSuccess) return LF_ERR_HIP;
+  // With frames to retrieve there are three launches: the pass over K; the frame means, with the
+  // pooling of Q riding along (nothing needs q_tilde before the third); the selection.
   const bool retrieve = b->k_frames < dm->m;
+  if (launch_pool(retrieve ? nullptr : Q, K, s, dm, qt, kt, dm->n_k, 0, dm->F, st) != hipSuccess) return LF_ERR_HIP;
   if (retrieve &&
-      lf_launch(lf_frame_mean_kernel, dim3((unsigned)(dm->H * dm->m)), dim3(dm->d), 0, st,
-                (const float*)kt, kh, dm->d, dm->nb, dm->n_k, dm->m, b->n_sink, 0, dm->m) != hipSuccess)
+      launch_frame_means(dm, kt, kh, dm->n_k, dm->m, b->n_sink, 0, dm->m,
+                         pool_args(Q, nullptr, s, dm, qt, nullptr, 1, 0, 0), st) != hipSuccess)
     return LF_ERR_HIP;
   return launch_select(b, dm, qt, kt, kh, dm->n_k, dm->m > 0 ? dm->m : 1, 0, indices, st) == hipSuccess
              ? LF_OK : LF_ERR_HIP;
@@ -504,9 +555,9 @@ int lf_launch_kcache_update(const void* K, const lf_shape* s, const lf_dims* dm,
   float* kh = kt + (size_t)dm->H * max_frames * dm->nb * dm->d;
   if (launch_pool(nullptr, K, s, dm, nullptr, kt, max_frames * dm->nb, frame0, frame1, st) != hipSuccess)
     return LF_ERR_HIP;
-  return lf_launch(lf_frame_mean_kernel, dim3((unsigned)(dm->H * (frame1 - frame0))), dim3(dm->d), 0, st,
-                   (const float*)kt, kh, dm->d, dm->nb, max_frames * dm->nb, max_frames, frame0, frame0,
-                   frame1 - frame0) == hipSuccess ? LF_OK : LF_ERR_HIP;
+  return launch_frame_means(dm, kt, kh, max_frames * dm->nb, max_frames, frame0, frame0, frame1 - frame0,
+                            pool_args(nullptr, nullptr, s, dm, nullptr, nullptr, 1, 0, 0), st) == hipSuccess
+             ? LF_OK : LF_ERR_HIP;
 }
 
 int lf_launch_select_cached(const void* Q, const void* Kcur, void* kcache, int max_frames,
