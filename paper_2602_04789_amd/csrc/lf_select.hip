@@ -322,8 +322,35 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   if (tid < D) qd[tid] = (double)qrow[tid];
   __syncthreads();
 
-  // Eq. 8: frame-level scores against the candidate frames M = [n_sink, F_h - n_win).
   const bool retrieve = a.k_frames < a.m;
+  const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.kt_rows * D);
+
+  // With one candidate per thread (E == 1), Eq. 10 is taken in two parts.  The candidates of
+  // the sink, window and (when they compete) current frames are known before any frame score
+  // is: there are n_cand - k_frames nb of them, position (= rank by block id among the
+  // candidates) below n_sink nb or from (n_sink + k_frames) nb on, and in list slot i >= n_sink
+  // + k_frames sits frame F_h - n_tf + i.  They are scored now, by the threads counted down
+  // from the last one, i.e. by the wavefronts that have nothing to do while the first one
+  // scores the frames; the candidates of the retrieved frames follow below, on the threads
+  // counted up from the first.  The two sets of threads are disjoint (n_cand <= 256).
+  const int ret_b = (E == 1 && retrieve) ? a.k_frames * a.nb : 0;
+  const bool need_scores = a.k_blocks < a.n_cand;
+  float s1 = -INFINITY;   // E == 1: this thread's score and its candidate's position
+  int p1 = -1;
+  if (E == 1) {
+    uint32_t* keys = reinterpret_cast<uint32_t*>(xs);
+    keys[tid] = 0u;       // pads must hold 0 (see the ranking below)
+    if (tid < a.n_cand) sel[tid] = 0;
+    const int slot = kThreads - 1 - tid, sink_b = a.n_sink * a.nb;
+    if (need_scores && slot < a.n_cand - ret_b) {
+      p1 = slot < sink_b ? slot : slot + ret_b;
+      const int i = p1 / a.nb;
+      const int frame = i < a.n_sink ? i : a.F_h - a.n_tf + i;
+      s1 = dot_quad_major<D>(qd, kth, (uint32_t)(frame * a.nb + p1 % a.nb), a.kt_rows);
+    }
+  }
+
+  // Eq. 8: frame-level scores against the candidate frames M = [n_sink, F_h - n_win).
   if (retrieve) {
     const float4* khh = reinterpret_cast<const float4*>(a.kh + (int64_t)h * a.kh_rows * D) + a.kh_row0;
     for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh, (uint32_t)c, a.kh_rows);
@@ -349,11 +376,17 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   __syncthreads();
 
   // Eq. 10: block-level scores over B_r, candidates in ascending block id; candidate
-  // e*256 + tid is element e of this thread.
+  // e*256 + tid is element e of this thread (E > 1; for E == 1 see above).
   float s[E];
   int p[E];
-  {
-    const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.kt_rows * D);
+  if (E == 1) {
+    if (need_scores && tid < ret_b) {
+      p1 = a.n_sink * a.nb + tid;
+      s1 = dot_quad_major<D>(qd, kth, (uint32_t)(flist[p1 / a.nb] * a.nb + p1 % a.nb), a.kt_rows);
+    }
+    s[0] = s1;
+    p[0] = p1;
+  } else {
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const int i = e * kThreads + tid;
@@ -376,10 +409,10 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
     // own + later positions with a key > its own; for a wavefront the positions before its
     // first lane are all earlier and those after its last lane all later, so only the 64
     // positions of its own lanes need the position compared.  Pads hold 0, which no key is below.
-    uint32_t* keys = reinterpret_cast<uint32_t*>(xs);   // [256], 16-byte aligned
-    const uint32_t mine = rank_key32(s[0]);
-    keys[tid] = tid < a.n_cand ? mine : 0u;
+    uint32_t* keys = reinterpret_cast<uint32_t*>(xs);   // [256], 16-byte aligned, zeroed above
+    if (p[0] >= 0) keys[p[0]] = rank_key32(s[0]);
     __syncthreads();
+    const uint32_t mine = keys[tid];
     const int w0 = __builtin_amdgcn_readfirstlane(tid & ~63);
     if (w0 < a.n_cand) {
       // four counters, so that a compare and the add that takes its carry need not be neighbours
