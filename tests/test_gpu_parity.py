@@ -237,6 +237,50 @@ def test_attention_list_edge_cases(gpu):
     assert float(Obuf[:, 0].abs().max()) == 0 and float(Obuf[:, :, w.head_dim:].abs().max()) == 0
 
 
+@pytest.mark.parametrize("frame_len,head_dim", [(200, 128), (232, 128), (224, 64)])
+def test_lists_whose_half_tile_counts_differ(gpu, frame_len, head_dim):
+    """A listed block of at most 32 tokens is one step of the kernel, a longer one two, an id out
+    of range none, and the two query blocks of a workgroup take the longer one's step count: lists
+    of equal length whose neighbours differ in all of that (only tail blocks, only full blocks, a
+    mix with invalid ids, hardly any valid id), with tails of 8, 40 and 32 tokens, two query
+    frames so that a short query block sits inside the chunk, and more than one decode pass."""
+    torch, lf = gpu
+    w = synth.small_ragged(frame_len=frame_len, chunk_idx=4, heads=2, head_dim=head_dim)
+    x = synth.make_inputs(w)
+    Qf, Kf, Vf = (_host_f32(x[k]) for k in "QKV")
+    Q, K, V = (_dev(torch, x[k]) for k in "QKV")
+    nb, n_q, n_k = w.blocks_per_frame, w.frames_per_chunk * w.blocks_per_frame, w.frames * w.blocks_per_frame
+    tails = np.arange(nb - 1, n_k, nb, dtype=np.int32)
+    full = np.array([c for c in range(n_k) if c % nb != nb - 1], np.int32)
+    rng = np.random.default_rng(7)
+    for L in (6, 300):
+        lists = np.empty((w.heads, n_q, L), np.int32)
+        for h in range(w.heads):
+            for r in range(n_q):
+                kind = (r + h) % 4
+                if kind == 0:
+                    row = rng.choice(tails, L)
+                elif kind == 1:
+                    row = rng.choice(full, L)
+                elif kind == 2:
+                    row = rng.integers(-3, n_k + 3, L).astype(np.int32)
+                else:
+                    row = np.full(L, -1, np.int32)
+                    row[rng.integers(0, L)] = rng.integers(0, n_k)
+                lists[h, r] = row
+        print(f"half-tile counts: n={frame_len} d={head_dim} list length {L}", flush=True)
+        out = lf.lf_sparse_attn(Q, K, V, torch.from_numpy(lists).cuda(), w.frame_len, w.block)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().astype(np.float64)
+        for h in range(w.heads):
+            for r in range(n_q):
+                kept = [int(c) for c in lists[h, r] if 0 <= c < n_k]
+                lo, hi = O.block_token_range(r, w.frame_len, w.block)
+                ref = O.sparse_attention_block(Qf[h], Kf[h], Vf[h], r, kept, w.frame_len, w.block)
+                err = np.abs(got[h, lo:hi] - ref)
+                assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, (L, h, r, err.max())
+
+
 @pytest.mark.parametrize("scale", [0.25, 1.0, 4.0])
 def test_attention_with_extreme_logits(gpu, scale):
     """Logits far outside the usual range (softmax_scale 0.25, 1 and 4 instead of 1/sqrt(d) =
