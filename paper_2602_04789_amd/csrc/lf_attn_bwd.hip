@@ -249,12 +249,17 @@ __global__ __launch_bounds__(kThreads, 2) void lf_attn_bwd_q_kernel(BwdArgs a) {
   };
   // P' = exp2(s c - lse2), dS' = P' (dP' - delta), packed to bfloat16 in the B-operand layout of
   // the accumulating product; accumulator i is stream row 8 (i/4) + 4 kg + i%4
-  auto probs = [&](const f32x16& sacc, const f32x16& pacc, int cnt, bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+  auto probs = [&](f32x16& sacc, const f32x16& pacc, int cnt, bf16x8 (&dsf)[2]) __attribute__((always_inline)) {
+    // stream rows past a short half tile's count were loaded as zeros: their scores become -inf
+    // (P' = 0); a full half tile, the common case, skips this
+    if (cnt < 32) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (8 * (i >> 2) + 4 * kg + (i & 3) >= cnt) sacc[i] = -INFINITY;
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int row = 8 * (i >> 2) + 4 * kg + (i & 3);
-      float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -mine.x));
-      if (row >= cnt) p = 0.0f;
+      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -mine.x));
       dsf[i >> 3][i & 7] = (__bf16)(p * (pacc[i] - mine.y));
     }
   };
@@ -531,7 +536,14 @@ __global__ __launch_bounds__(kKvThreads, 2) void lf_attn_bwd_kv_kernel(BwdArgs a
     // role 0 on half tile t (stage cur): S', P' (handed over), dV^T += dO^T P'
     auto p_step = [&](int t) __attribute__((always_inline)) {
       const int cnt = half(t).y;
-      const f32x16 sacc = product(buf[cur]);
+      f32x16 sacc = product(buf[cur]);
+      // stream rows past a short half tile's count were loaded as zeros (scores and statistics
+      // alike): their scores become -inf (P' = 0); a full half tile, the common case, skips this
+      if (cnt < 32) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i >> 2) + 4 * kg + (i & 3) >= cnt) sacc[i] = -INFINITY;
+      }
       bf16x8 pf[2];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -539,10 +551,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void lf_attn_bwd_kv_kernel(BwdArgs a
         stats4(st[cur][wave], g, lse, dl);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int i = 4 * g + e, row = 8 * g + 4 * kg + e;
-          float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse[e]));
-          if (row >= cnt) p = 0.0f;
-          pf[i >> 3][i & 7] = (__bf16)p;
+          const int i = 4 * g + e;
+          pf[i >> 3][i & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[i], a.c, -lse[e]));
         }
       }
       ph[t & 1][pair][0][lane] = __builtin_bit_cast(uint4, pf[0]);
