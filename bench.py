@@ -305,16 +305,17 @@ def time_training(torch, lf, synth, w, Q, K, V, idx, out, flops, n=20):
     bwd = lambda: lf.lf_sparse_attn_bwd(Q, K, V, out, dO, lse2, idx, w.frame_len, w.block, workspace=bws)
     t_ms = []
     for fn in (fwd, bwd):
-        for _ in range(3):
-            fn()
+        # untimed calls, then the timed ones right behind them (no idle gap in between: after one
+        # the first launches run at a lower clock for a few milliseconds); the median
         te = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n)]
-        torch.cuda.synchronize()
+        for _ in range(10):
+            fn()
         for e in te:
             e[0].record()
             fn()
             e[1].record()
         torch.cuda.synchronize()
-        t_ms.append(float(np.mean([e[0].elapsed_time(e[1]) for e in te])))
+        t_ms.append(float(np.median([e[0].elapsed_time(e[1]) for e in te])))
     tf = 2.5 * flops / (t_ms[1] * 1e-3) / 1e12
     return {"what": "lf_sparse_attn_fwd (O and log-sum-exp) and lf_sparse_attn_bwd (dQ, dK, dV) on the same "
                     "lists; backward work counted as 2.5 x the forward's kept flops",
@@ -576,18 +577,17 @@ def main():
     del kc_all
     if b.current_mandatory and not args.headline_only and not use_split:
         aws = torch.empty(lf.lf_attn_workspace_bytes(sh), dtype=torch.uint8, device="cuda")
-        # 30 calls back to back between two events (a call is two launches; bracketing every
-        # single call with events of its own adds the events' cost to both)
-        se = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        for _ in range(5):
+        # 20 untimed calls, then 30 timed ones right behind them (no idle gap in between: after
+        # one the first launches run at a lower clock for a few milliseconds); the median
+        se = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(30)]
+        for _ in range(20):
             lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b, O=out, workspace=aws)
-        torch.cuda.synchronize()
-        se[0].record()
-        for _ in range(30):
+        for e in se:
+            e[0].record()
             lf.lf_sparse_attn_split(Q, K, V, idx, w.frame_len, w.block, b, O=out, workspace=aws)
-        se[1].record()
+            e[1].record()
         torch.cuda.synchronize()
-        s_ms = se[0].elapsed_time(se[1]) / 30
+        s_ms = float(np.median([e[0].elapsed_time(e[1]) for e in se]))
         res["attn_split"] = {"what": "lf_sparse_attn_split: dense kernel over the current chunk + list-driven kernel "
                                      "over the retrieved blocks", "ms": s_ms,
                              "achieved": flops / (s_ms * 1e-3) / 1e12, "unit": "TFLOP/s"}
