@@ -178,6 +178,40 @@ def measured_peaks(torch, select_bytes: int):
     return out
 
 
+def run_fill_scan(torch, lf, synth, workload):
+    """The attention kernel on the same shapes with 3 .. 28 heads, i.e. from fewer workgroups than
+    compute units to four per unit: how its time grows with the fill of the chip."""
+    from dataclasses import replace
+    base = _workloads()[workload]()
+    rows = []
+    for heads in (3, 6, 7, 9, 10, 12, 13, 14, 16, 20, 24, 27, 28):
+        w = replace(base, heads=heads)
+        x = synth.make_inputs(w)
+        Q, K, V = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QKV")
+        b = lf.lf_chunk_budget(w.chunk_idx, lf.make_schedule(w.schedule))
+        idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+        out = torch.empty_like(Q)
+        flops = kept_flops(idx.cpu().numpy(), w)
+        ts = []
+        for _ in range(3):
+            for _ in range(5):
+                lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                lf.lf_sparse_attn(Q, K, V, idx, w.frame_len, w.block, O=out)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / 20)
+        n_wg = (heads * w.frames_per_chunk * w.blocks_per_frame + 1) // 2
+        rows.append({"heads": heads, "workgroups": n_wg, "ms": min(ts), "us_per_head": min(ts) * 1e3 / heads,
+                     "tflops": flops / (min(ts) * 1e-3) / 1e12})
+        del Q, K, V, out, idx
+    print(json.dumps({"fill_scan": rows, "workload": base.name,
+                      "what": "lf_sparse_attn alone, 20 launches back to back, minimum of 3 rounds; two query "
+                              "blocks per workgroup, two workgroups per compute unit at a time"}))
+
+
 def run_sensitivity(torch, lf, synth, workload):
     """How much the attention kernel lengthens when one unit gets more work per step: probe builds
     of the library (same kernel plus redundant work for one unit, results discarded, output
@@ -417,6 +451,8 @@ def main():
     ap.add_argument("--sensitivity", action="store_true",
                     help="time the probe build of the attention kernel with extra work per unit "
                          "(prints its own JSON line and exits)")
+    ap.add_argument("--fill-scan", action="store_true",
+                    help="time the attention kernel alone at 3 .. 28 heads (prints its own JSON line and exits)")
     ap.add_argument("--micro-only", action="store_true",
                     help="run only the micro-benchmarks (streaming read, MFMA loop) and exit")
     ap.add_argument("--cold", action="store_true",
@@ -442,6 +478,8 @@ def main():
         return
     if args.sensitivity:
         return run_sensitivity(torch, lf, synth, args.workload)
+    if args.fill_scan:
+        return run_fill_scan(torch, lf, synth, args.workload)
     if args.workload == "rollout":
         if args.steps == 100 and args.warmup == 20:   # the defaults are sized for one chunk
             args.steps, args.warmup = 5, 1
