@@ -124,6 +124,12 @@ SMALL = {
     "tail_33": lambda: synth.small_ragged(frame_len=97, chunk_idx=3, heads=2, head_dim=64),
     "many_frames": lambda: synth.small_ragged(frame_len=64, chunk_idx=40, frames_per_chunk=2,
                                               heads=1, k_frames=5, n_sink=2, n_win=3),
+    # 216 candidates of which 200 are known before the frame ranking (10 sink + 10 window frames and
+    # 5 competing current frames of 8 blocks): the early scoring reaches down into the wavefront
+    # that also scores the frames and the retrieved blocks
+    "known_200_of_216": lambda: synth.small_ragged(frame_len=500, chunk_idx=6, frames_per_chunk=5, heads=1,
+                                                   k_frames=2, n_sink=10, n_win=10, current_mandatory=0,
+                                                   ratio_of=synth.OF_CANDIDATES, keep_fixed=0.5),
     # candidate sets wider than one per thread: 320, 560 and 1040 candidate blocks
     "wide_320": lambda: synth.small_ragged(frame_len=500, chunk_idx=28, frames_per_chunk=5, heads=1,
                                            k_frames=35, n_sink=2, n_win=3,
