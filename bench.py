@@ -679,7 +679,12 @@ def main():
     if cold is not None:
         res["cold_after_1gib_stream"] = cold
     if not args.no_measured_peaks:
-        res["measured"] = measured_peaks(torch, int(sel_bytes))
+        res["measured"] = m = measured_peaks(torch, int(sel_bytes))
+        # the same two fractions against what this chip reached in this run: the register-only
+        # matrix loop on pseudo-random operands, and the plain streaming read of the same bytes
+        res["roofline"]["frac_of_measured_mfma_loop_random_operands"] = \
+            res["roofline"]["achieved"] / m["mfma_bf16_loop_random_operands_tflops"]
+        res["select"]["frac_of_measured_stream_read"] = res["select"]["achieved"] / m["stream_read_select_bytes_gbps"]
     if not args.no_per_config:
         per = []
         names = [n for n in ("first_chunk", "mid_rollout", "last_chunk", "paper5s_last", "paper15s_late")
