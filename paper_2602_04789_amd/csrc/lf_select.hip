@@ -5,8 +5,10 @@
 //   lf_frame_mean_kernel  frame means of the candidate frames (Eq. 7, framewise); the block
 //                         means of Q ride along in the same launch.
 //   lf_select_kernel      per (head, query block): frame scores (Eq. 8), frame top-k
-//                         (Eq. 9), block scores (Eq. 10), block top-k by a bitonic sort over
-//                         lane shuffles and LDS (Eq. 11), ascending index list (Eq. 12).
+//                         (Eq. 9), block scores (Eq. 10), block top-k (Eq. 11: by counting
+//                         the keys that rank before each candidate when there are at most
+//                         256 of them, by a bitonic sort over lane shuffles and LDS beyond
+//                         that), ascending index list (Eq. 12).
 //
 // Arithmetic contract (see lf.h): block sums in binary64 (exact for in-range bf16 inputs,
 // so the reduction tree is free), means rounded to float32; scores are binary64 sums over
