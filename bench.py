@@ -178,6 +178,50 @@ def measured_peaks(torch, select_bytes: int):
     return out
 
 
+def run_select_phases(torch, lf, synth, workload):
+    """Where the selection kernel's time goes: the probe build of the library notes the wall clock
+    (100 MHz) at the kernel's phase boundaries in every workgroup; lists are those of the product."""
+    import ctypes
+    from paper_2602_04789_amd import build as B
+    path = B.probe_lib("stamps")
+    if not os.path.exists(path):
+        sys.exit(f"bench.py: {path} not built")
+    w = _workloads()[workload]()
+    x = synth.make_inputs(w)
+    Q, K = (torch.from_numpy(x[k]).view(torch.bfloat16).cuda() for k in "QK")
+    b = lf.lf_chunk_budget(w.chunk_idx, lf.make_schedule(w.schedule))
+    ref = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    lf._lib, lf._LIB_PATH = None, path
+    lf.load()
+    raw = ctypes.CDLL(path)
+    for _ in range(5):
+        idx = lf.lf_select_mask(Q, K, w.frame_len, w.block, b)
+    torch.cuda.synchronize()
+    out = np.zeros(4096 * 8, dtype=np.uint64)
+    rc = raw.lf_probe_select_stamps(ctypes.c_void_p(out.ctypes.data))
+    if rc != 0:
+        sys.exit(f"bench.py: lf_probe_select_stamps failed ({rc})")
+    n_wg = min(4096, w.heads * w.frames_per_chunk * w.blocks_per_frame)
+    st = out.reshape(4096, 8)[:n_wg, :7].astype(np.int64)
+    names = ["load q_tilde", "frame scores (+ scores of the known candidates)", "frame ranking and list",
+             "block scores of the retrieved frames", "block ranking", "compaction and store"]
+    phases = []
+    for i, name in enumerate(names):
+        d = (st[:, i + 1] - st[:, i]) * 10.0
+        phases.append({"phase": name, "mean_ns": float(d.mean()), "median_ns": float(np.median(d)),
+                       "p90_ns": float(np.percentile(d, 90)), "max_ns": float(d.max())})
+    tot = (st[:, 6] - st[:, 0]) * 10.0
+    t0 = st[:, 0].min()
+    print(json.dumps({"select_phases": phases, "workload": w.name, "workgroups": int(n_wg),
+                      "workgroup_ns": {"mean": float(tot.mean()), "max": float(tot.max())},
+                      "start_spread_ns": {"median": float(np.median(st[:, 0] - t0) * 10.0),
+                                          "max": float((st[:, 0] - t0).max() * 10.0)},
+                      "first_start_to_last_end_ns": float((st[:, 6].max() - t0) * 10.0),
+                      "lists_equal_product": bool(torch.equal(idx, ref)),
+                      "what": "probe build (LF_PROBE_STAMPS): wall clock of 10 ns ticks read by thread 0 of every "
+                              "workgroup at the phase boundaries; last of 5 launches"}))
+
+
 def run_fill_scan(torch, lf, synth, workload):
     """The attention kernel on the same shapes with 3 .. 28 heads, i.e. from fewer workgroups than
     compute units to four per unit: how its time grows with the fill of the chip."""
@@ -451,6 +495,8 @@ def main():
     ap.add_argument("--sensitivity", action="store_true",
                     help="time the probe build of the attention kernel with extra work per unit "
                          "(prints its own JSON line and exits)")
+    ap.add_argument("--select-phases", action="store_true",
+                    help="phase times of the selection kernel from its probe build (prints its own JSON line and exits)")
     ap.add_argument("--fill-scan", action="store_true",
                     help="time the attention kernel alone at 3 .. 28 heads (prints its own JSON line and exits)")
     ap.add_argument("--micro-only", action="store_true",
@@ -480,6 +526,8 @@ def main():
         return run_sensitivity(torch, lf, synth, args.workload)
     if args.fill_scan:
         return run_fill_scan(torch, lf, synth, args.workload)
+    if args.select_phases:
+        return run_select_phases(torch, lf, synth, args.workload)
     if args.workload == "rollout":
         if args.steps == 100 and args.warmup == 20:   # the defaults are sized for one chunk
             args.steps, args.warmup = 5, 1

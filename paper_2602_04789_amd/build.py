@@ -80,6 +80,12 @@ def build(verbose: bool = False, extra_device_flags=()) -> str:
              COMMON + DEVICE + PER_FILE["lf_attn.hip"])
         _run([hipcc, "-shared", "-o", probe_lib(tag)] + [o for o in objs if os.path.basename(o) != "lf_attn_hip.o"] + [pobj] +
              ["--offload-arch=gfx950"])
+    # probe build for `bench.py --select-phases`: the selection kernel with wall-clock stamps at its
+    # phase boundaries (LF_PROBE_STAMPS), everything else the same objects
+    sobj = os.path.join(OBJ, "lf_select_probe_stamps_hip.o")
+    _run([hipcc, "-c", os.path.join(CSRC, "lf_select.hip"), "-o", sobj, "-DLF_PROBE_STAMPS"] + COMMON + DEVICE)
+    _run([hipcc, "-shared", "-o", probe_lib("stamps")] + [o for o in objs if os.path.basename(o) != "lf_select_hip.o"] +
+         [sobj] + ["--offload-arch=gfx950"])
     # the benchmark's micro-benchmarks: a library of their own, not linked into the product
     bobj = os.path.join(OBJ, "lf_bench_hip.o")
     _run([hipcc, "-c", os.path.join(CSRC, "lf_bench.hip"), "-o", bobj] + COMMON + DEVICE)

@@ -306,8 +306,21 @@ __device__ __forceinline__ uint32_t rank_key32(float score) {
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
+// Probe build only (liblf_hsa_probe_stamps.so, for `bench.py --select-phases`): thread 0 of the
+// first 4096 workgroups notes the 100 MHz wall clock at the phase boundaries of the kernel, to
+// see where its time goes.  The lists are unchanged; the product build has none of this.
+#ifdef LF_PROBE_STAMPS
+__device__ unsigned long long g_stamps[4096 * 8];
+#define LF_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_stamps[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#define LF_STAMP_SYNC() __syncthreads()
+#else
+#define LF_STAMP(i)
+#define LF_STAMP_SYNC()
+#endif
+
 template <int D, int E>
 __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(SelectArgs a) {
+  LF_STAMP(0);
   // LDS carved from one dynamic allocation sized for this call (see select_lds_bytes()).
   extern __shared__ double lds_raw[];
   double* qd = lds_raw;                                         // [D]
@@ -323,6 +336,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   const float* qrow = a.qt + ((int64_t)h * a.n_q + r) * D;
   if (tid < D) qd[tid] = (double)qrow[tid];
   __syncthreads();
+  LF_STAMP(1);   // q_tilde is in LDS
 
   const bool retrieve = a.k_frames < a.m;
   const float4* kth = reinterpret_cast<const float4*>(a.kt + (int64_t)h * a.kt_rows * D);
@@ -358,6 +372,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
     for (int c = tid; c < a.m; c += kThreads) fscore[c] = dot_quad_major<D>(qd, khh, (uint32_t)c, a.kh_rows);
   }
   __syncthreads();
+  LF_STAMP(2);   // frame scores (and, with one candidate per thread, the scores of the known candidates)
 
   // Eq. 9: T_r = top-k frames U sink U window (U current, appended below).
   for (int t = tid; t < a.F_h; t += kThreads) {
@@ -376,6 +391,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
   if (!a.current_mandatory)
     for (int t = tid; t < a.f; t += kThreads) flist[a.n_tf + t] = a.F_h + t;
   __syncthreads();
+  LF_STAMP(3);   // frame ranking and frame list
 
   // Eq. 10: block-level scores over B_r, candidates in ascending block id; candidate
   // e*256 + tid is element e of this thread (E > 1; for E == 1 see above).
@@ -403,6 +419,8 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
     }
   }
 
+  LF_STAMP_SYNC();
+  LF_STAMP(4);   // block scores
   // Eq. 11: top-k blocks, J_r = the candidates of rank < k_blocks.  With at most one
   // candidate per thread the rank is counted directly (how many keys are larger, keys read
   // as LDS broadcasts); larger candidate sets are sorted, after which index = rank.
@@ -454,6 +472,7 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
     for (int i = tid; i < a.n_cand; i += kThreads) sel[i] = 1;
   }
   __syncthreads();
+  LF_STAMP(5);   // block ranking
 
   // Eq. 12 as a sorted list: kept candidates in ascending id, then the mandatory current blocks.
   int32_t* out = a.indices + ((int64_t)h * a.n_q + r) * a.list_len;
@@ -461,6 +480,8 @@ __global__ __launch_bounds__(kThreads, (E <= 2 ? 4 : 2)) void lf_select_kernel(S
     wave_compact(sel, a.n_cand, [&](int pos, int i) { out[pos] = flist[i / a.nb] * a.nb + i % a.nb; });
   if (a.current_mandatory)
     for (int i = tid; i < a.f * a.nb; i += kThreads) out[a.k_blocks + i] = a.F_h * a.nb + i;
+  LF_STAMP_SYNC();
+  LF_STAMP(6);   // compaction and store
 }
 
 }  // namespace
@@ -622,6 +643,14 @@ namespace {
 constexpr int kMaxDevices = 64;
 void* g_scratch_ptr[kMaxDevices];   // zero-initialised; written once per device (same value if raced)
 }
+
+#ifdef LF_PROBE_STAMPS
+// Copies the stamps of the last selection launch to host memory: [4096][8] uint64, entries 0..6 of
+// a workgroup as noted above.  Returns 0 or a hipError_t.
+extern "C" int lf_probe_select_stamps(void* host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_stamps), sizeof(unsigned long long) * 4096 * 8);
+}
+#endif
 
 int lf_static_scratch(void** out) {
   int dev = -1;

@@ -43,6 +43,9 @@ def test_probe_and_benchmark_libraries_load(lib):
     for tag in build.PROBES:
         probe = C.CDLL(build.probe_lib(tag))
         assert hasattr(probe, "lf_sparse_attn") and hasattr(probe, "lf_sparse_attn_bwd")
+    stamps = C.CDLL(build.probe_lib("stamps"))   # selection kernel with phase stamps
+    assert hasattr(stamps, "lf_select_mask") and hasattr(stamps, "lf_probe_select_stamps")
+    assert not hasattr(lib, "lf_probe_select_stamps")   # the product build carries no stamps
     assert hasattr(C.CDLL(build.BENCH_LIB), "lfb_stream_read")
 
 
